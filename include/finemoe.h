@@ -1,0 +1,171 @@
+/*
+ * finemoe.h - C ABI of the MI355X (gfx950) MoE-layer hot path under FineEP token
+ * scheduling (FineMoE, arXiv 2511.16947).
+ *
+ * One MoE layer's expert computation: given top-K routing, a scheduler assigns every
+ * (token, expert) pair to one of G logical expert-parallel ranks so that the largest
+ * per-rank load is minimal (Section 4.1, Eq. 1), routes token ranges to replicas
+ * (Section 4.2, Algorithm 1), and each rank's share then runs as a permute, a grouped
+ * SwiGLU expert FFN and a weighted combine (Section 3, "Runtime").  All G ranks run one
+ * after another on the current GPU; there is no communication.
+ *
+ * Conventions
+ *   - Every function returns an int status (FINE_OK = 0, negative = error).  Nothing
+ *     throws, aborts or prints.
+ *   - Every array pointer is a DEVICE pointer on the current HIP device unless its name
+ *     ends in _host.  The caller owns every buffer; the library allocates no device
+ *     memory and keeps no state between calls.  Scratch comes from `ws`, whose size is
+ *     given by fine_workspace_bytes(); `ws` must be 256-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on that stream and never synchronise the device.
+ *   - Outputs are fully overwritten, except the weight-gradient buffers of
+ *     fine_backward(), which are governed by `accumulate`.
+ *   - Notation: T tokens, d hidden size, f expert FFN width, E experts, K = top-K,
+ *     G ranks, P = T*K pairs; pair id p = t*K + k.  Token t lives on source rank
+ *     src(t) = t / (T/G) (G must divide T).  Row-major everywhere.
+ *   - dtype: FINE_F32 (all data fp32) or FINE_BF16 (data bf16, fp32 accumulation, one
+ *     rounding per stored tensor).  For FINE_BF16 d and f must be multiples of 64.
+ *   - Limits: 1 <= K <= E <= 1024, 1 <= G <= 64, K <= 32, P < 2^31 / max(d, 2f).
+ */
+#ifndef FINEMOE_H
+#define FINEMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    FINE_OK = 0,
+    FINE_INVALID_ARG = -1,       /* null pointer, K > E, G does not divide T, bad dtype, misaligned */
+    FINE_UNSUPPORTED = -2,       /* a shape outside the limits above */
+    FINE_WORKSPACE_TOO_SMALL = -3,
+    FINE_INFEASIBLE = -4,        /* placement: an expert without any replica */
+    FINE_HIP_ERROR = -5          /* see fine_last_hip_error() */
+};
+
+enum { FINE_F32 = 0, FINE_BF16 = 1 };
+
+/* flags */
+enum {
+    FINE_FLAG_LOCALITY = 1,      /* run the local pass of Algorithm 1 (lines 4-9) first */
+    FINE_FLAG_SIMPLE_FFN = 2,    /* debugging: plain tiled FMA kernels instead of MFMA */
+    FINE_FLAG_TILE_SHIFT = 8,    /* bits 8-9: row tile of the MFMA kernels, 0 = chosen from the */
+    FINE_FLAG_TILE_MASK = 0x300  /*   shape, 1 = 64 rows, 2 = 128 rows, 3 = 256 rows           */
+};
+
+/* which entry point a workspace is for */
+enum { FINE_WS_TOPK = 0, FINE_WS_SCHED = 1, FINE_WS_FFN = 2, FINE_WS_BACKWARD = 3 };
+
+typedef struct {
+    int32_t T, d, f, E, K, G;
+    int32_t dtype;               /* FINE_F32 or FINE_BF16 */
+    int32_t flags;               /* FINE_FLAG_* */
+} fine_shape;
+
+/* Library version (major*100 + minor). */
+int fine_version(void);
+
+/* The hipError_t (as int) of the last failed HIP call on this thread, 0 if none. */
+int fine_last_hip_error(void);
+
+/* Bytes of scratch the entry point `which` needs for this shape (0 on a bad shape). */
+size_t fine_workspace_bytes(const fine_shape* shape, int which);
+
+/*
+ * Gate (Section 2.1: the gate network assigns each token to its top-K experts).
+ * logits[t][e] = sum_i x[t][i] * w_router[i][e] + bias[e] in fp32; topk_idx[t][:] = the K
+ * experts with the largest logits in descending order (equal logits: lower index first);
+ * topk_w[t][:] = softmax over those K logits (fp32).
+ *   x [T,d] dtype, w_router [d,E] dtype, bias [E] fp32 or NULL,
+ *   topk_idx [T,K] int32 out, topk_w [T,K] fp32 out.
+ */
+int fine_topk(const fine_shape* shape, const void* x, const void* w_router, const float* bias,
+              int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Token scheduling (Sections 4.1-4.2).  In:
+ *   topk_idx [T,K] int32, values in [0,E), distinct within a token;
+ *   place [E,G] uint8 (non-zero = expert e has a replica on rank g, i.e. g in G_EDP^e), or
+ *         NULL = every expert on every rank.
+ * Out (all int32):
+ *   load [E]        load_e, pairs per expert (Table 1)
+ *   input_eg [E,G]  input_e^g, pairs of expert e whose token lives on rank g
+ *   x_eg [E,G]      replica loads x_e^g: the integer optimum of Eq. 1 that is
+ *                   lexicographically greatest (e ascending, then g ascending) among all
+ *                   integer solutions whose largest rank load is the optimum M*
+ *   max_load [1]    M* = ceil(m), m the optimal value of Eq. 1 (= Eq. 3)
+ *   pair_dst [P]    rank that computes pair p: Algorithm 1 with every loop in ascending
+ *                   rank order and tokens taken in ascending token index
+ *   row_of_pair [P] row of pair p in the permuted buffer: pairs sorted by
+ *                   (pair_dst, expert, token)
+ *   pair_of_row [P] the inverse permutation
+ *   seg_off [G,E+1] first row of segment (rank g, expert e); seg_off[g][E] = end of rank g
+ *   rank_off [G+1]  first row of each rank; rank_off[G] = P
+ * With place == NULL the replica loads have a closed form (cut the expert-sorted pair
+ * sequence into chunks of M* = ceil(P/G)); with a placement the optimum is found by
+ * exact integer max-flows on the device.  Returns FINE_INFEASIBLE only for what the host
+ * can see (it cannot read `place`): an expert whose row of `place` is empty receives no
+ * replica and its pairs are reported by max_load[0] = -1.
+ */
+int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
+               int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
+               int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+               int32_t* seg_off, int32_t* rank_off,
+               void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Permutation (Section 4.4: replicate tokens by top-K and sort them before dispatch).
+ * x_perm[row] = x[pair_of_row[row] / K].   x [T,d] dtype -> x_perm [P,d] dtype.
+ */
+int fine_permute(const fine_shape* shape, const void* x, const int32_t* pair_of_row,
+                 void* x_perm, void* stream);
+
+/*
+ * Expert computation of one rank (Section 3: each GPU processes its received tokens with
+ * its local expert replicas), or of all ranks in order when rank == -1.  For every
+ * segment (rank, e) with rows r0 = seg_off[rank][e] .. seg_off[rank][e+1]:
+ *   A = X W_gate[e], B = X W_up[e], H = silu(A) * B (rounded to dtype), Y = H W_down[e].
+ *   x_perm [P,d]; w_gate, w_up [E,d,f]; w_down [E,f,d]; y_perm [P,d] out;
+ *   act_save NULL or [P,2f] dtype out: columns [0,f) = A, [f,2f) = B (for fine_backward).
+ * Rows of other ranks are left untouched.
+ */
+int fine_grouped_ffn(const fine_shape* shape, int32_t rank,
+                     const void* x_perm, const void* w_gate, const void* w_up, const void* w_down,
+                     const int32_t* seg_off, void* y_perm, void* act_save,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Combine (Section 2.1: the selected experts' results are aggregated; Section 3: tokens
+ * return to their source).  out[t] = sum_k topk_w[t][k] * y_perm[row_of_pair[t*K+k]],
+ * summed in fp32 in ascending k and rounded once.   out [T,d] dtype.
+ */
+int fine_combine(const fine_shape* shape, const void* y_perm, const int32_t* row_of_pair,
+                 const float* topk_w, void* out, void* stream);
+
+/*
+ * Backward of permute + expert computation + combine for rank `rank` (-1 = all ranks in
+ * ascending order).  The paper aggregates the gradients of an expert's replicas with a
+ * data-parallel all-reduce (Section 2.2); on one GPU the replicas share one fp32
+ * accumulator per expert, added in ascending rank order.
+ *   d_out [T,d] dtype; x_perm, y_perm [P,d]; act_save [P,2f] or NULL (then recomputed);
+ *   d_x [T,d] dtype out (rank == -1 only; per-rank calls leave it untouched and fill the
+ *        rank's rows of the internal d_x_perm, see DESIGN notes in the Python binding);
+ *   d_topk_w [T,K] fp32 out: <d_out[t], y_perm[row]> (entries of other ranks untouched);
+ *   d_w_gate, d_w_up [E,d,f] fp32, d_w_down [E,f,d] fp32: accumulate != 0 adds to the
+ *        buffers, accumulate == 0 overwrites them (experts without rows get zeros).
+ */
+int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
+                  const void* x_perm, const void* y_perm, const void* act_save,
+                  const void* w_gate, const void* w_up, const void* w_down,
+                  const int32_t* row_of_pair, const int32_t* pair_of_row, const int32_t* seg_off,
+                  const float* topk_w,
+                  void* d_x, float* d_topk_w, float* d_w_gate, float* d_w_up, float* d_w_down,
+                  int accumulate, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FINEMOE_H */

@@ -1,0 +1,145 @@
+// Internal declarations shared by the HIP translation units of libfinemoe.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/finemoe.h"
+
+namespace fine {
+
+typedef __hip_bfloat16 bf16;
+
+extern thread_local int g_last_hip_error;
+
+inline int check_hip(hipError_t e) {
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        return FINE_HIP_ERROR;
+    }
+    return FINE_OK;
+}
+
+#define FINE_TRY(expr)                      \
+    do {                                    \
+        int _rc = (expr);                   \
+        if (_rc != FINE_OK) return _rc;     \
+    } while (0)
+
+#define FINE_LAUNCH_CHECK() FINE_TRY(fine::check_hip(hipGetLastError()))
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// bf16 <-> fp32 on raw bits (round to nearest even), usable on host and device.
+__host__ __device__ inline float bf16_bits_to_float(uint16_t h) {
+    union { uint32_t u; float f; } v;
+    v.u = ((uint32_t)h) << 16;
+    return v.f;
+}
+__host__ __device__ inline uint16_t float_to_bf16_bits(float f) {
+    union { uint32_t u; float f; } v;
+    v.f = f;
+    uint32_t u = v.u;
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Element access helpers for the two storage types.
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    __device__ static inline float load(const float* p) { return *p; }
+    __device__ static inline void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {   // bf16 bits
+    __device__ static inline float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
+    __device__ static inline void store(uint16_t* p, float v) { *p = float_to_bf16_bits(v); }
+};
+
+inline size_t elem_size(int dtype) { return dtype == FINE_F32 ? 4 : 2; }
+
+// ---------------------------------------------------------------------------
+// Scheduler workspace layout (all offsets in bytes from ws, 256-byte aligned).
+// ---------------------------------------------------------------------------
+struct SchedWs {
+    size_t bitmap;     // uint64 [E][W]    bit t%64 of word t/64: token t chose expert e
+    size_t cum;        // int32  [E][W+1]  exclusive prefix of popcounts over words
+    size_t inpre;      // int32  [E][G]    pairs of expert e on source ranks < g
+    size_t Y;          // int32  [E][G][G] Algorithm 1 transfer table
+    size_t Ypre;       // int32  [E][G][G] Ypre[e][g][h] = sum_{g'<g} Y[e][g'][h]
+    size_t solver;     // int32  scratch of the general-placement solver
+    size_t total;
+    int W;
+};
+SchedWs sched_ws_layout(const fine_shape& s);
+
+// Work list of the grouped GEMMs: one entry per (segment, row tile).
+struct TileEntry {
+    int32_t expert;
+    int32_t row0;      // first row of the tile (absolute row of the permuted buffer)
+    int32_t rows;      // valid rows in the tile (1..BM)
+    int32_t seg_rows;  // rows of the whole segment
+};
+
+struct FfnWs {
+    size_t h;          // dtype [P][f]
+    size_t tiles;      // TileEntry [max_tiles] followed by int32 count
+    size_t count;
+    size_t total;
+    int max_tiles;
+};
+FfnWs ffn_ws_layout(const fine_shape& s);
+
+struct BwdWs {
+    size_t act;        // dtype [P][2f]   recomputed pre-activations when act_save == NULL
+    size_t dy;         // dtype [P][d]    w * d_out, permuted
+    size_t dact;       // dtype [P][2f]   dA | dB
+    size_t h;          // dtype [P][f]
+    size_t dxp;        // dtype [P][d]
+    size_t tiles;
+    size_t count;
+    size_t total;
+    int max_tiles;
+};
+BwdWs bwd_ws_layout(const fine_shape& s);
+
+// ---------------------------------------------------------------------------
+// Launchers (each enqueues on `st` and returns a FINE_* status).
+// ---------------------------------------------------------------------------
+int launch_topk(const fine_shape& s, const void* x, const void* w_router, const float* bias,
+                int32_t* topk_idx, float* topk_w, hipStream_t st);
+
+int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place,
+                 int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
+                 int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+                 int32_t* seg_off, int32_t* rank_off, char* ws, hipStream_t st);
+
+int launch_permute(const fine_shape& s, const void* x, const int32_t* pair_of_row, void* x_perm, hipStream_t st);
+int launch_combine(const fine_shape& s, const void* y_perm, const int32_t* row_of_pair,
+                   const float* topk_w, void* out, hipStream_t st);
+int launch_combine_bwd(const fine_shape& s, const void* d_out, const void* y_perm,
+                       const int32_t* pair_of_row, const float* topk_w,
+                       void* dy_perm, float* d_topk_w, hipStream_t st);
+int launch_permute_bwd(const fine_shape& s, const void* dx_perm, const int32_t* row_of_pair,
+                       void* d_x, hipStream_t st);
+
+int launch_tile_map(const fine_shape& s, const int32_t* seg_off, int rank_lo, int rank_hi, int BM,
+                    TileEntry* tiles, int32_t* count, int max_tiles, hipStream_t st);
+
+int launch_ffn_simple(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm,
+                      const void* wg, const void* wu, const void* wd, const int32_t* seg_off,
+                      void* y_perm, void* act_save, char* ws, hipStream_t st);
+int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm,
+                    const void* wg, const void* wu, const void* wd, const int32_t* seg_off,
+                    void* y_perm, void* act_save, char* ws, hipStream_t st);
+
+int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, const void* y_perm,
+                    const void* act_save, const void* wg, const void* wu, const void* wd,
+                    const int32_t* row_of_pair, const int32_t* pair_of_row, const int32_t* seg_off,
+                    const float* topk_w, void* d_x, float* d_topk_w, float* d_wg, float* d_wu,
+                    float* d_wd, int accumulate, char* ws, hipStream_t st);
+
+}  // namespace fine

@@ -1,0 +1,61 @@
+"""CPU-only checks of the C ABI: the library builds, loads and exports every
+symbol the header declares; argument validation that needs no GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2511_16947_amd as fm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "finemoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fine_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(fm.LIB_PATH):
+        from paper_2511_16947_amd import build
+        build.build()
+    return fm.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(fm.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_workspace_queries(lib):
+    assert fm.fine_version() >= 100
+    s = fm.Shape(256, 128, 256, 8, 2, 4, fm.FINE_F32)
+    for which in (fm.WS_TOPK, fm.WS_SCHED, fm.WS_FFN, fm.WS_BACKWARD):
+        assert fm.fine_workspace_bytes(s, which) > 0
+    assert fm.fine_workspace_bytes(s, 99) == 0
+    # G does not divide T, K > E, bf16 with d not a multiple of 64: rejected
+    assert fm.fine_workspace_bytes(fm.Shape(250, 128, 256, 8, 2, 4, fm.FINE_F32), fm.WS_SCHED) == 0
+    assert fm.fine_workspace_bytes(fm.Shape(256, 128, 256, 2, 3, 4, fm.FINE_F32), fm.WS_SCHED) == 0
+    assert fm.fine_workspace_bytes(fm.Shape(256, 100, 256, 8, 2, 4, fm.FINE_BF16), fm.WS_FFN) == 0
+
+
+def test_null_pointers_are_rejected_without_touching_the_gpu(lib):
+    s = fm.Shape(256, 128, 256, 8, 2, 4, fm.FINE_F32).c()
+    rc = lib.fine_permute(ctypes.byref(s), None, None, None, None)
+    assert rc == fm.FINE_INVALID_ARG
+    rc = lib.fine_combine(ctypes.byref(s), None, None, None, None, None)
+    assert rc == fm.FINE_INVALID_ARG
+    bad = fm.Shape(256, 128, 256, 8, 9, 4, fm.FINE_F32).c()
+    assert lib.fine_permute(ctypes.byref(bad), None, None, None, None) == fm.FINE_INVALID_ARG
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(fm, "_lib", None)
+    monkeypatch.setattr(fm, "LIB_PATH", str(tmp_path / "libfinemoe.so"))
+    with pytest.raises(FileNotFoundError):
+        fm.fine_version()

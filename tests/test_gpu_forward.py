@@ -1,0 +1,146 @@
+"""GPU parity of the forward hot path against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_16947_amd as fm
+import workloads as wl
+from oracle import moe, router, sched
+from gpu_common import (GpuLayer, check_router, check_schedule_against_oracle, max_rel_err, to64, tol_for,
+                        weights_of_factory)
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+# ------------------------------------------------------------------ scheduler
+
+SCHED_CASES = [
+    # T, E, K, G, skew
+    (256, 8, 2, 4, 1.0),
+    (96, 5, 3, 4, 1.5),        # T/G = 24: source blocks straddle 64-token words
+    (640, 128, 8, 8, 1.2),     # many experts, several words per source
+    (2048, 256, 8, 32, 1.0),
+    (4096, 64, 2, 16, 2.0),
+    (64, 1, 1, 1, 0.0),        # degenerate: one expert, one rank
+    (64, 3, 3, 64, 0.0),       # one token per rank, every token picks every expert
+    (1000, 7, 1, 8, 3.0),      # P not divisible by 64, heavy skew
+]
+
+
+@pytest.mark.parametrize("locality", [True, False])
+@pytest.mark.parametrize("case", SCHED_CASES)
+def test_sched_full_placement_bit_exact(case, locality):
+    T, E, K, G, skew = case
+    idx = wl.random_topk(T, E, K, seed=T + E, skew=skew)
+    shape = fm.Shape(T, 64, 64, E, K, G, fm.FINE_BF16, fm.FLAG_LOCALITY if locality else 0)
+    sb = fm.SchedBuffers(shape, DEV)
+    print("sched case", case, "locality", locality, flush=True)
+    sb.run(shape, torch.from_numpy(idx).to(DEV))
+    torch.cuda.synchronize()
+    want = check_schedule_against_oracle(sb, idx, E, G, None, locality)
+    rows = np.diff(want["rank_off"])
+    assert rows.max() == -(-T * K // G)                  # the balance criterion: max load = ceil(P/G)
+
+
+def test_sched_is_deterministic_across_runs():
+    T, E, K, G = 4096, 128, 8, 8
+    idx = torch.from_numpy(wl.random_topk(T, E, K, seed=1, skew=1.3)).to(DEV)
+    shape = fm.Shape(T, 64, 64, E, K, G)
+    a, b = fm.SchedBuffers(shape, DEV), fm.SchedBuffers(shape, DEV)
+    a.run(shape, idx)
+    b.run(shape, idx)
+    torch.cuda.synchronize()
+    for name in ("x_eg", "pair_dst", "row_of_pair", "pair_of_row", "seg_off"):
+        assert torch.equal(getattr(a, name), getattr(b, name))
+
+
+# ------------------------------------------------------------------ whole layer, small
+
+def small_cfgs():
+    c = wl.CONFIGS
+    return [
+        c["cfg1_tiny_f32"],
+        wl.scaled(c["cfg2_mixtral"], name="cfg2_small", T=1024, d=256, f=448),      # ragged n tile (448 = 3.5 x 128)
+        wl.scaled(c["cfg3_finegrained"], name="cfg3_small", T=512, d=128, f=192),
+        wl.scaled(c["cfg4_dsv3"], name="cfg4_small", T=512, d=192, f=128),
+        wl.scaled(c["cfg5_train"], name="cfg5_small", T=2048, d=128, f=256),
+        wl.scaled(c["cfg1_tiny_f32"], name="f32_odd", T=60, d=50, f=70, E=5, K=3, G=3),  # nothing a multiple of a tile
+    ]
+
+
+@pytest.mark.parametrize("cfg", small_cfgs(), ids=lambda c: c.name)
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, "simple"])
+def test_layer_forward_elementwise(cfg, tile):
+    if cfg.dtype == "f32" and tile != 0:
+        pytest.skip("tile variants are for the bf16 MFMA kernels")
+    flags = fm.FLAG_LOCALITY
+    if tile == "simple":
+        flags |= fm.FLAG_SIMPLE_FFN
+    else:
+        flags |= tile << 8
+    print("layer case", cfg.name, "tile", tile, flush=True)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, flags)
+    layer.forward()
+
+    check_router(cfg, inp, layer.topk_idx, layer.topk_w)
+    idx = layer.topk_idx.cpu().numpy()
+    w = to64(layer.topk_w)
+    want = check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G)
+
+    # permute: pure data movement, bit exact
+    xp = layer.x_perm.cpu()
+    assert torch.equal(xp, inp.x.cpu()[torch.from_numpy(want["pair_of_row"].astype(np.int64) // cfg.K)])
+
+    # expert computation and combine against the unscheduled dense definition, given the
+    # library's own routing (indices and fp32 weights)
+    weights_of = weights_of_factory(inp)
+    ref_out = moe.dense_reference_by_expert(to64(inp.x), idx, w, weights_of)
+    ref_y = moe.grouped_ffn(moe.permute(to64(inp.x), want["pair_of_row"], cfg.K), want["seg_off"], weights_of)
+    tol = tol_for(cfg)
+    assert max_rel_err(to64(layer.y_perm), ref_y) <= tol
+    assert max_rel_err(to64(layer.out), ref_out) <= tol
+
+    # per-rank calls give the same bits as the all-ranks call
+    y_all = layer.y_perm.clone()
+    layer.y_perm.zero_()
+    for r in range(cfg.G):
+        layer.ffn(r)
+    torch.cuda.synchronize()
+    assert torch.equal(layer.y_perm, y_all)
+
+
+def test_act_save_holds_the_preactivations():
+    cfg = wl.scaled(wl.CONFIGS["cfg2_mixtral"], name="cfg2_small", T=512, d=128, f=256)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp)
+    layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+    layer.forward()
+    want = sched.schedule(layer.topk_idx.cpu().numpy(), cfg.E, cfg.G)
+    xp = moe.permute(to64(inp.x), want["pair_of_row"], cfg.K)
+    got = to64(layer.act_save)
+    for g in range(cfg.G):
+        for e in range(cfg.E):
+            lo, hi = want["seg_off"][g, e], want["seg_off"][g, e + 1]
+            if hi > lo:
+                a = xp[lo:hi] @ to64(inp.w_gate[e])
+                b = xp[lo:hi] @ to64(inp.w_up[e])
+                assert max_rel_err(got[lo:hi, :cfg.f], a) <= 2e-2
+                assert max_rel_err(got[lo:hi, cfg.f:], b) <= 2e-2
+
+
+def test_bad_arguments_return_errors():
+    s = fm.Shape(256, 128, 256, 8, 2, 4, fm.FINE_BF16)
+    x = torch.zeros(256, 128, dtype=torch.bfloat16, device=DEV)
+    idx = torch.zeros(512, dtype=torch.int32, device=DEV)
+    xp = torch.zeros(512, 128, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(fm.FineError) as ei:
+        fm.fine_permute(s, x, idx, None)
+    assert ei.value.code == fm.FINE_INVALID_ARG
+    with pytest.raises(fm.FineError) as ei:
+        fm.fine_grouped_ffn(s, 7, xp, xp, xp, xp, idx, xp, None, torch.zeros(1024, dtype=torch.uint8, device=DEV))
+    assert ei.value.code == fm.FINE_INVALID_ARG      # rank out of range
+    with pytest.raises(fm.FineError) as ei:
+        fm.fine_grouped_ffn(s, 0, xp, xp, xp, xp, idx, xp, None, torch.zeros(1024, dtype=torch.uint8, device=DEV))
+    assert ei.value.code == fm.FINE_WORKSPACE_TOO_SMALL
