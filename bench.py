@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""One-GPU benchmark of the scheduled MoE-layer hot path.
+
+A step = one pass of the whole forward hot path over one synthetic batch that is
+already resident in HBM: gate top-K, token scheduling, permute, grouped SwiGLU expert
+FFN for every logical rank (one rank after another), combine; for the training
+workload (cfg5_train) the backward pass as well.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2_mixtral]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2_mixtral")
+    ap.add_argument("--ffn", choices=["per_rank", "fused"], default="per_rank",
+                    help="per_rank: one fine_grouped_ffn call per logical rank (default); fused: one call for all")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--detail-iters", type=int, default=10)
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the G logical ranks execute one after another on it); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2511_16947_amd as fm
+    import workloads as wl
+
+    cfg = wl.CONFIGS[args.config]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    t_gen = time.time()
+    inp = wl.make_inputs(cfg, dev)
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+
+    shape = fm.shape_of(cfg)
+    s = shape
+    topk_idx = torch.empty(s.T, s.K, dtype=torch.int32, device=dev)
+    topk_w = torch.empty(s.T, s.K, dtype=torch.float32, device=dev)
+    sb = fm.SchedBuffers(s, dev)
+    x_perm = torch.empty(s.P, s.d, dtype=s.torch_dtype, device=dev)
+    y_perm = torch.empty(s.P, s.d, dtype=s.torch_dtype, device=dev)
+    out = torch.empty(s.T, s.d, dtype=s.torch_dtype, device=dev)
+    ws_ffn = fm.alloc_workspace(s, fm.WS_FFN, dev)
+    do_bwd = cfg.backward and not args.no_backward
+    if do_bwd:
+        ws_bwd = fm.alloc_workspace(s, fm.WS_BACKWARD, dev)
+        d_x = torch.empty(s.T, s.d, dtype=s.torch_dtype, device=dev)
+        d_topk_w = torch.empty(s.T, s.K, dtype=torch.float32, device=dev)
+        d_wg = torch.empty(s.E, s.d, s.f, dtype=torch.float32, device=dev)
+        d_wu = torch.empty(s.E, s.d, s.f, dtype=torch.float32, device=dev)
+        d_wd = torch.empty(s.E, s.f, s.d, dtype=torch.float32, device=dev)
+
+    def st_topk():
+        fm.fine_topk(s, inp.x, inp.w_router, inp.bias, topk_idx, topk_w)
+
+    def st_sched():
+        sb.run(s, topk_idx, None)
+
+    def st_permute():
+        fm.fine_permute(s, inp.x, sb.pair_of_row, x_perm)
+
+    def st_ffn_rank(r, shp=s):
+        fm.fine_grouped_ffn(shp, r, x_perm, inp.w_gate, inp.w_up, inp.w_down, sb.seg_off, y_perm, None, ws_ffn)
+
+    def st_ffn():
+        if args.ffn == "fused":
+            st_ffn_rank(-1)
+        else:
+            for r in range(s.G):
+                st_ffn_rank(r)
+
+    def st_combine():
+        fm.fine_combine(s, y_perm, sb.row_of_pair, topk_w, out)
+
+    def st_backward():
+        fm.fine_backward(s, -1, inp.d_out, x_perm, y_perm, None, inp.w_gate, inp.w_up, inp.w_down, sb.row_of_pair,
+                         sb.pair_of_row, sb.seg_off, topk_w, d_x, d_topk_w, d_wg, d_wu, d_wd, False, ws_bwd)
+
+    stages = [("topk", st_topk), ("sched", st_sched), ("permute", st_permute), ("ffn", st_ffn), ("combine", st_combine)]
+    if do_bwd:
+        stages.append(("backward", st_backward))
+
+    def step():
+        for _, fn in stages:
+            fn()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    fwd_flop = 6.0 * s.P * s.d * s.f
+    step_flop = fwd_flop * (3.0 if do_bwd else 1.0)
+    value = step_flop / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-stage and per-rank detail (events on the launch stream) -------------------------
+    def time_ms(fn, iters):
+        evs = []
+        for _ in range(iters):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in evs]
+
+    it = args.detail_iters
+    stage_ms = {name: float(np.median(time_ms(fn, it))) for name, fn in stages}
+    if args.ffn == "per_rank":
+        stage_ms["ffn_fused_call"] = float(np.median(time_ms(lambda: st_ffn_rank(-1), it)))
+    rank_ms = [float(np.median(time_ms(lambda r=r: st_ffn_rank(r), it))) for r in range(s.G)]
+    rank_rows = np.diff(sb.rank_off.cpu().numpy()).astype(np.int64)
+    load = sb.load.cpu().numpy().astype(np.int64)
+
+    # ---- roofline of the dominant kernel: GEMM 1 (X [Wg|Wu] + SwiGLU), one launch per rank ----
+    only1 = fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | fm.FLAG_ONLY_GEMM1)
+    none = fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | fm.FLAG_ONLY_GEMM1 | fm.FLAG_ONLY_GEMM2)
+    roofline = None
+    if cfg.dtype == "bf16":
+        g1 = [float(np.mean(time_ms(lambda r=r: st_ffn_rank(r, only1), it))) for r in range(s.G)]
+        tm = [float(np.mean(time_ms(lambda r=r: st_ffn_rank(r, none), it))) for r in range(s.G)]
+        dur_ms = float(np.mean(g1) - np.mean(tm))                    # the tile-map kernel alone is subtracted
+        flops_per_launch = 4.0 * float(rank_rows.mean()) * s.d * s.f  # rows of the rank x (gate + up) x 2
+        achieved = flops_per_launch / (dur_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "k_ffn_gemm<EPI=0> (X[Wg|Wu]+SwiGLU), one launch per rank",
+                    "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                    "avg_launch_ms": round(dur_ms, 4), "flops_per_launch": flops_per_launch}
+
+    es = 4 if cfg.dtype == "f32" else 2
+    gbs = {
+        "permute_GBs": round((2.0 * s.P * s.d * es + 4.0 * s.P) / (stage_ms["permute"] * 1e-3) / 1e9, 1),
+        "combine_GBs": round((s.P * s.d * es + 8.0 * s.P + s.T * s.d * es) / (stage_ms["combine"] * 1e-3) / 1e9, 1),
+        "topk_GBs": round((s.T * s.d * es + s.d * s.E * es + 8.0 * s.P) / (stage_ms["topk"] * 1e-3) / 1e9, 1),
+    }
+    ffn_ms_total = float(np.sum(rank_ms))
+    detail = {
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "ffn_TFLOPs_per_rank_calls": round(fwd_flop / (ffn_ms_total * 1e-3) / 1e12, 2),
+        "layer_TFLOPs_sched_permute_ffn_combine": round(
+            fwd_flop / ((stage_ms["sched"] + stage_ms["permute"] + stage_ms["ffn"] + stage_ms["combine"]) * 1e-3) / 1e12, 2),
+        "rank_ffn_ms_max_over_mean": round(max(rank_ms) / (ffn_ms_total / s.G), 4),
+        "rank_rows_max_over_mean": round(float(rank_rows.max() / rank_rows.mean()), 4),
+        "hottest_over_mean_expert_load": round(float(load.max() / load.mean()), 3),
+        "vanilla_ep_rows_max_over_mean": round(float(
+            np.add.reduceat(load, np.arange(0, s.E, max(1, s.E // s.G)))[:s.G].max() / (s.P / s.G)), 3) if s.E >= s.G else None,
+        "rank_ffn_ms": [round(v, 4) for v in rank_ms],
+        "input_gen_s": round(t_gen, 2),
+        **gbs,
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = run_cpu_baseline(cfg, inp, topk_idx, topk_w)
+
+    line = {
+        "metric": "MoE layer TFLOP/s per GPU (gate top-K + sched + permute + grouped GEMM + combine%s)" % (
+            " + backward" if do_bwd else ""),
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "T": s.T, "d": s.d, "f": s.f, "E": s.E, "K": s.K, "G": s.G,
+                   "placement": "every expert on every rank", "ffn_calls": args.ffn, "backward": bool(do_bwd)},
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "detail": detail,
+    }
+    print(json.dumps(line))
+
+
+def run_cpu_baseline(cfg, inp, topk_idx, topk_w):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload: the
+    scheduler on the full routing table, and the dense per-token layer (fp64) on the
+    first n tokens, n sized for roughly 10-30 s of host work."""
+    import numpy as np
+    import torch
+
+    from oracle import moe, sched
+
+    cores = len(os.sched_getaffinity(0))
+    idx = topk_idx.cpu().numpy()
+    w = topk_w.double().cpu().numpy()
+    t0 = time.perf_counter()
+    sched.schedule(idx, cfg.E, cfg.G)
+    t_sched = time.perf_counter() - t0
+    per_token = 6.0 * cfg.K * cfg.d * cfg.f
+    n = int(min(cfg.T, max(16, 1.5e12 // per_token)))
+    tokens = np.arange(n)
+    x64 = inp.x[:n].double().cpu().numpy()
+    x_full = np.zeros((cfg.T, cfg.d))
+    x_full[:n] = x64
+
+    def weights_of(e):
+        return (inp.w_gate[e].double().cpu().numpy(), inp.w_up[e].double().cpu().numpy(),
+                inp.w_down[e].double().cpu().numpy())
+
+    t0 = time.perf_counter()
+    moe.dense_reference_by_expert(x_full, idx, w, weights_of, tokens=tokens)
+    t_ffn = time.perf_counter() - t0
+    flops = per_token * n
+    return {"value": round(flops / t_ffn / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "dense per-token fp64 layer on the first %d of %d tokens (%.2f s, includes fp64 weight "
+                      "conversion); scheduler oracle on the full routing table took %.2f s"
+                      % (n, cfg.T, t_ffn, t_sched)}
+
+
+if __name__ == "__main__":
+    main()

@@ -52,6 +52,8 @@ enum { FINE_F32 = 0, FINE_BF16 = 1 };
 enum {
     FINE_FLAG_LOCALITY = 1,      /* run the local pass of Algorithm 1 (lines 4-9) first */
     FINE_FLAG_SIMPLE_FFN = 2,    /* debugging: plain tiled FMA kernels instead of MFMA */
+    FINE_FLAG_ONLY_GEMM1 = 4,    /* measurement: fine_grouped_ffn runs only X[Wg|Wu] + SwiGLU   */
+    FINE_FLAG_ONLY_GEMM2 = 8,    /* measurement: fine_grouped_ffn runs only H Wd (H from ws)     */
     FINE_FLAG_TILE_SHIFT = 8,    /* bits 8-9: row tile of the MFMA kernels, 0 = chosen from the */
     FINE_FLAG_TILE_MASK = 0x300  /*   shape, 1 = 64 rows, 2 = 128 rows, 3 = 256 rows           */
 };

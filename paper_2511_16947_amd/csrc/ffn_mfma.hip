@@ -142,9 +142,11 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     }
     const int blocks_per_cu = (lds <= 80 * 1024) ? 2 : 1;
     const int grid = 256 * blocks_per_cu;
+    if (!(s.flags & FINE_FLAG_ONLY_GEMM2))
     hipLaunchKernelGGL(k1, dim3(grid), dim3(256), lds, st, (const uint16_t*)x_perm, s.d, (const uint16_t*)wg,
                        (const uint16_t*)wu, (size_t)s.d * s.f, s.d, s.f, h, s.f, (uint16_t*)act_save, tiles, count);
     FINE_LAUNCH_CHECK();
+    if (!(s.flags & FINE_FLAG_ONLY_GEMM1))
     hipLaunchKernelGGL(k2, dim3(grid), dim3(256), lds, st, (const uint16_t*)h, s.f, (const uint16_t*)wd,
                        (const uint16_t*)nullptr, (size_t)s.f * s.d, s.f, s.d, (uint16_t*)y_perm, s.d,
                        (uint16_t*)nullptr, tiles, count);
