@@ -142,3 +142,25 @@ def layer_loss(x, topk_idx, topk_w, weights_of, d_out):
     """L = sum(out * d_out) of the dense definition (for finite differences)."""
     out = dense_reference_by_expert(x, topk_idx, topk_w, weights_of)
     return float(np.sum(out * np.asarray(d_out, dtype=np.float64)))
+
+
+def weight_grad_columns(x_rows, dy_rows, Wg, Wu, Wd, cols):
+    """Selected columns of one expert's weight gradients without forming whole
+    [n,f] matrices: for every j in cols returns
+        d_w_gate[:, j], d_w_up[:, j]  (length d)   and   d_w_down[j, :]  (length d),
+    from the same formulas as backward_dense, restricted to column j of
+    a, b, h and dh.  x_rows[n,d] are the expert's input rows, dy_rows[n,d] the
+    gradients of its outputs (already scaled by the combine weights)."""
+    x_rows = np.asarray(x_rows, dtype=np.float64)
+    dy_rows = np.asarray(dy_rows, dtype=np.float64)
+    out = {}
+    for j in cols:
+        a = x_rows @ Wg[:, j]
+        b = x_rows @ Wu[:, j]
+        s = _sigmoid(a)
+        h = a * s * b
+        dh = dy_rows @ Wd[j, :]
+        da = dh * b * s * (1.0 + a * (1.0 - s))
+        db = dh * a * s
+        out[int(j)] = (x_rows.T @ da, x_rows.T @ db, h @ dy_rows)
+    return out

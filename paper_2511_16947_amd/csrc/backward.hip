@@ -1,14 +1,268 @@
-// Backward of permute + grouped FFN + combine.
-#include "common.h"
+// Backward of permute + grouped SwiGLU FFN + combine (bf16 data, fp32 accumulation).
+//
+//   dY[row]   = w[pair] * dOut[token]                    d_topk_w = <dOut[token], y_perm[row]>
+//   dH        = dY Wd^T                                  (grouped, k contiguous in both operands)
+//   dA        = dH * b * s * (1 + a (1 - s)),  dB = dH * a * s,  H = a s b   with s = sigmoid(a)
+//   dXp       = dA Wg^T + dB Wu^T                        (one GEMM over k = 2f)
+//   dWd_e    += H^T dY,  dWg_e += X^T dA,  dWu_e += X^T dB   (contraction over the rows of expert
+//               e on every rank, ranks in ascending order: the replicas' gradients, which the
+//               paper sums with a data-parallel all-reduce, share one fp32 accumulator here)
+//   dX[token] = sum_k dXp[row(token, k)]
+#include "gemm_mfma.h"
 
 namespace fine {
+
+namespace {
+
+using namespace mfma;
+
+// ---- dH = dY Wd^T with the SwiGLU backward epilogue -------------------------------------
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(256) void k_bwd_dh(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
+                                                const uint16_t* __restrict__ act, int d, int f,
+                                                uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
+                                                const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int ntn = (f + BN - 1) / BN, ntm = *count, total = ntm * ntn;
+    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
+    for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
+        const TileEntry te = tiles[work % ntm];
+        const int n0 = (work / ntm) * BN;
+        const uint16_t* W = wd + (size_t)te.expert * f * d;
+        LoaderKC<BM> la;
+        la.init([&](int r) { return dy + (size_t)(te.row0 + min(r, te.rows - 1)) * d; });
+        LoaderKC<BN> lb;
+        lb.init([&](int n) { return W + (size_t)min(n0 + n, f - 1) * d; });
+        f32x16 acc[WM][WN];
+        zero_acc<WM, WN>(acc);
+        k_loop<WAVES_M, WAVES_N, WM, WN>(
+            d / BK, smem, acc, [&](int kt) { la.load(kt * BK); lb.load(kt * BK); },
+            [&](char* a, char* b) { la.store(a); lb.store(b); });
+        const int col_in = acc_col();
+        static_for<WM>([&](auto mi) {
+            static_for<16>([&](auto r) {
+                const int m = (wm * WM + mi) * 32 + acc_row(r);
+                if (m < te.rows) {
+                    const size_t row = (size_t)te.row0 + m;
+                    static_for<WN>([&](auto ni) {
+                        const int col = n0 + (wn * WN + ni) * 32 + col_in;
+                        if (col < f) {
+                            const float dh = acc[mi.value][ni.value][r.value];
+                            const float a = bf16_bits_to_float(act[row * (size_t)(2 * f) + col]);
+                            const float b = bf16_bits_to_float(act[row * (size_t)(2 * f) + f + col]);
+                            const float s = 1.f / (1.f + __expf(-a));
+                            dact[row * (size_t)(2 * f) + col] = float_to_bf16_bits(dh * b * s * (1.f + a * (1.f - s)));
+                            dact[row * (size_t)(2 * f) + f + col] = float_to_bf16_bits(dh * a * s);
+                            h[row * (size_t)f + col] = float_to_bf16_bits(a * s * b);
+                        }
+                    });
+                }
+            });
+        });
+    }
+}
+
+// ---- dXp = [dA | dB] [Wg | Wu]^T --------------------------------------------------------------
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(256) void k_bwd_dx(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
+                                                const uint16_t* __restrict__ wu, int d, int f,
+                                                uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
+                                                const int32_t* __restrict__ count) {
+    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int ntn = (d + BN - 1) / BN, ntm = *count, total = ntm * ntn;
+    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int nkf = f / BK;
+    for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
+        const TileEntry te = tiles[work % ntm];
+        const int n0 = (work / ntm) * BN;
+        const uint16_t* Wg = wg + (size_t)te.expert * d * f;
+        const uint16_t* Wu = wu + (size_t)te.expert * d * f;
+        LoaderKC<BM> la;
+        la.init([&](int r) { return dact + (size_t)(te.row0 + min(r, te.rows - 1)) * (2 * f); });
+        LoaderKC<BN> lb;     // pointers into Wg; the Wu half is reached through a constant offset
+        lb.init([&](int n) { return Wg + (size_t)min(n0 + n, d - 1) * f; });
+        const ptrdiff_t to_up = Wu - Wg;
+        f32x16 acc[WM][WN];
+        zero_acc<WM, WN>(acc);
+        k_loop<WAVES_M, WAVES_N, WM, WN>(
+            2 * nkf, smem, acc,
+            [&](int kt) {
+                la.load(kt * BK);
+                lb.load(kt < nkf ? (ptrdiff_t)kt * BK : to_up + (ptrdiff_t)(kt - nkf) * BK);
+            },
+            [&](char* a, char* b) { la.store(a); lb.store(b); });
+        const int col_in = acc_col();
+        static_for<WM>([&](auto mi) {
+            static_for<16>([&](auto r) {
+                const int m = (wm * WM + mi) * 32 + acc_row(r);
+                if (m < te.rows) {
+                    const size_t row = (size_t)te.row0 + m;
+                    static_for<WN>([&](auto ni) {
+                        const int col = n0 + (wn * WN + ni) * 32 + col_in;
+                        if (col < d) dxp[row * (size_t)d + col] = float_to_bf16_bits(acc[mi.value][ni.value][r.value]);
+                    });
+                }
+            });
+        });
+    }
+}
+
+// ---- weight gradients: out[e][m][n] (+)= sum over the rows of expert e of A[row][m] * B[row][n] ----
+struct WgradProblem {
+    const uint16_t* A; int lda; int M;     // A[row][m], m contiguous
+    const uint16_t* B; int ldb; int N;     // B[row][n], n contiguous
+    float* out;                            // [E][M][N]
+};
+
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1, WgradProblem p2,
+                                               const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
+    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int t0 = cdiv_dev(p0.M, BM) * cdiv_dev(p0.N, BN);
+    const int t1 = cdiv_dev(p1.M, BM) * cdiv_dev(p1.N, BN);
+    const int t2 = cdiv_dev(p2.M, BM) * cdiv_dev(p2.N, BN);
+    const int per_expert = t0 + t1 + t2;
+    const int total = per_expert * E;
+    for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
+        const int e = work / per_expert;
+        int j = work - e * per_expert;
+        WgradProblem p = p0;
+        if (j >= t0 + t1) { p = p2; j -= t0 + t1; }
+        else if (j >= t0) { p = p1; j -= t0; }
+        const int ntm = cdiv_dev(p.M, BM);
+        const int m0 = (j % ntm) * BM, n0 = (j / ntm) * BN;
+        LoaderMC<BM> la;
+        la.init([&](int r8) { return p.A + min(m0 + 8 * r8, p.M - 8); }, (size_t)p.lda);
+        LoaderMC<BN> lb;
+        lb.init([&](int r8) { return p.B + min(n0 + 8 * r8, p.N - 8); }, (size_t)p.ldb);
+        // k-tiles: 64 rows at a time through the expert's segment on every rank, ascending
+        int nk = 0;
+        for (int g = 0; g < G; ++g)
+            nk += (seg_off[(size_t)g * (E + 1) + e + 1] - seg_off[(size_t)g * (E + 1) + e] + BK - 1) / BK;
+        int cur_g = -1, cur_k = 0, cur_hi = 0;
+        f32x16 acc[WM][WN];
+        zero_acc<WM, WN>(acc);
+        k_loop<WAVES_M, WAVES_N, WM, WN>(
+            nk, smem, acc,
+            [&](int) {
+                while (cur_k >= cur_hi) {          // advance to the next non-empty segment
+                    ++cur_g;
+                    cur_k = seg_off[(size_t)cur_g * (E + 1) + e];
+                    cur_hi = seg_off[(size_t)cur_g * (E + 1) + e + 1];
+                }
+                la.load(cur_k, cur_hi);
+                lb.load(cur_k, cur_hi);
+                cur_k += BK;
+            },
+            [&](char* a, char* b) { la.store(a); lb.store(b); });
+        float* out = p.out + (size_t)e * p.M * p.N;
+        const int col_in = acc_col();
+        static_for<WM>([&](auto mi) {
+            static_for<16>([&](auto r) {
+                const int m = m0 + (wm * WM + mi) * 32 + acc_row(r);
+                if (m < p.M) {
+                    static_for<WN>([&](auto ni) {
+                        const int col = n0 + (wn * WN + ni) * 32 + col_in;
+                        if (col < p.N) {
+                            float* dst = out + (size_t)m * p.N + col;
+                            *dst = accumulate ? *dst + acc[mi.value][ni.value][r.value] : acc[mi.value][ni.value][r.value];
+                        }
+                    });
+                }
+            });
+        });
+    }
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+int run_dgrad(const fine_shape& s, const uint16_t* dy, const uint16_t* act, const uint16_t* wg, const uint16_t* wu,
+              const uint16_t* wd, const int32_t* seg_off, uint16_t* dact, uint16_t* h, uint16_t* dxp,
+              TileEntry* tiles, int32_t* count, int max_tiles, hipStream_t st) {
+    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    FINE_TRY(launch_tile_map(s, seg_off, 0, s.G, BM, tiles, count, max_tiles, st));
+    const size_t lds = (size_t)2 * (BM + BN) * 128;
+    auto k1 = k_bwd_dh<WAVES_M, WAVES_N, WM, WN>;
+    auto k2 = k_bwd_dx<WAVES_M, WAVES_N, WM, WN>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k1, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
+        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
+        attr_done = true;
+    }
+    const int grid = 256 * ((lds <= 80 * 1024) ? 2 : 1);
+    hipLaunchKernelGGL(k1, dim3(grid), dim3(256), lds, st, dy, wd, act, s.d, s.f, dact, h, tiles, count);
+    FINE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k2, dim3(grid), dim3(256), lds, st, dact, wg, wu, s.d, s.f, dxp, tiles, count);
+    FINE_LAUNCH_CHECK();
+    return FINE_OK;
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+int run_wgrad(const fine_shape& s, const uint16_t* x_perm, const uint16_t* dy, const uint16_t* dact, const uint16_t* h,
+              const int32_t* seg_off, float* d_wg, float* d_wu, float* d_wd, int accumulate, hipStream_t st) {
+    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    const size_t lds = (size_t)2 * (BM + BN) * 128;
+    auto k = k_wgrad<WAVES_M, WAVES_N, WM, WN>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
+        attr_done = true;
+    }
+    WgradProblem pg{x_perm, s.d, s.d, dact, 2 * s.f, s.f, d_wg};
+    WgradProblem pu{x_perm, s.d, s.d, dact + s.f, 2 * s.f, s.f, d_wu};
+    WgradProblem pd{h, s.f, s.f, dy, s.d, s.d, d_wd};
+    const int grid = 256 * ((lds <= 80 * 1024) ? 2 : 1);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, st, pg, pu, pd, seg_off, s.E, s.G, accumulate);
+    FINE_LAUNCH_CHECK();
+    return FINE_OK;
+}
+
+}  // namespace
 
 int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, const void* y_perm,
                     const void* act_save, const void* wg, const void* wu, const void* wd,
                     const int32_t* row_of_pair, const int32_t* pair_of_row, const int32_t* seg_off,
                     const float* topk_w, void* d_x, float* d_topk_w, float* d_wg, float* d_wu,
                     float* d_wd, int accumulate, char* ws, hipStream_t st) {
-    return FINE_UNSUPPORTED;
+    if (s.dtype != FINE_BF16) return FINE_UNSUPPORTED;
+    const BwdWs L = bwd_ws_layout(s);
+    auto* dy = reinterpret_cast<uint16_t*>(ws + L.dy);
+    auto* dact = reinterpret_cast<uint16_t*>(ws + L.dact);
+    auto* h = reinterpret_cast<uint16_t*>(ws + L.h);
+    auto* dxp = reinterpret_cast<uint16_t*>(ws + L.dxp);
+    auto* tiles = reinterpret_cast<TileEntry*>(ws + L.tiles);
+    auto* count = reinterpret_cast<int32_t*>(ws + L.count);
+    const uint16_t* act = reinterpret_cast<const uint16_t*>(act_save);
+
+    FINE_TRY(launch_combine_bwd(s, d_out, y_perm, pair_of_row, topk_w, dy, d_topk_w, st));
+    if (act == nullptr) {      // recompute the pre-activations A | B
+        auto* act_ws = reinterpret_cast<uint16_t*>(ws + L.act);
+        FINE_TRY(launch_ffn_parts(s, 0, s.G, x_perm, wg, wu, wd, seg_off, h, nullptr, act_ws, tiles, count, L.max_tiles,
+                                  true, false, st));
+        act = act_ws;
+    }
+    const double P = (double)s.T * s.K;
+    const double seg_rows = (P / s.G) / ((double)s.E / s.G + 1.0);
+    int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
+    if (tile == 0) tile = seg_rows >= 384.0 ? 3 : (seg_rows >= 96.0 ? 2 : 1);
+#define FINE_DGRAD(WAM, WAN, WMM, WNN)                                                                        \
+    FINE_TRY((run_dgrad<WAM, WAN, WMM, WNN>(s, dy, act, (const uint16_t*)wg, (const uint16_t*)wu, (const uint16_t*)wd, \
+                                            seg_off, dact, h, dxp, tiles, count, L.max_tiles, st)))
+    if (tile == 3) FINE_DGRAD(2, 2, 4, 4);
+    else if (tile == 2) FINE_DGRAD(2, 2, 2, 4);
+    else FINE_DGRAD(1, 4, 2, 2);
+#undef FINE_DGRAD
+    // weight-gradient tiles span the weight matrices, not the segments
+    if (s.d >= 256 && s.f >= 256 && tile != 1)
+        FINE_TRY((run_wgrad<2, 2, 4, 4>(s, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+    else
+        FINE_TRY((run_wgrad<2, 2, 2, 2>(s, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+    FINE_TRY(launch_permute_bwd(s, dxp, row_of_pair, d_x, st));
+    return FINE_OK;
 }
 
 }  // namespace fine

@@ -136,6 +136,11 @@ int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x
                     const void* wg, const void* wu, const void* wd, const int32_t* seg_off,
                     void* y_perm, void* act_save, char* ws, hipStream_t st);
 
+int launch_ffn_parts(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, const void* wg,
+                     const void* wu, const void* wd, const int32_t* seg_off, void* h_buf, void* y_perm,
+                     void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, bool gemm1, bool gemm2,
+                     hipStream_t st);
+
 int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, const void* y_perm,
                     const void* act_save, const void* wg, const void* wu, const void* wd,
                     const int32_t* row_of_pair, const int32_t* pair_of_row, const int32_t* seg_off,

@@ -15,13 +15,6 @@ using namespace mfma;
 
 __device__ inline float silu_mul(float a, float b) { return a / (1.f + __expf(-a)) * b; }
 
-// Blocks are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the
-// work list so that blocks sharing an L2 also share operand tiles.
-__device__ inline int xcd_contiguous_id() {
-    const int b = blockIdx.x, n = gridDim.x;
-    return (n % 8 == 0) ? (b % 8) * (n / 8) + b / 8 : b;
-}
-
 // EPI 0: GEMM 1 (A = x_perm, B0/B1 = Wg/Wu [E,Kd,N]; C = H [P,N]; act [P,2N] optional)
 // EPI 1: GEMM 2 (A = H, B0 = Wd [E,Kd,N]; C = y_perm [P,N])
 template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
@@ -35,8 +28,6 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
     static_assert(WAVES_M * WAVES_N == 4, "4 waves");
     static_assert(EPI != 0 || WN % 2 == 0, "gate/up pairs");
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    auto sA = [&](int buf) { return smem + buf * (BM * 128); };
-    auto sB = [&](int buf) { return smem + 2 * BM * 128 + buf * (BN * 128); };
 
     const int ntn = (N + BNC - 1) / BNC;
     const int ntm = *count;
@@ -68,69 +59,49 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
 
-        la.load(0);
-        lb.load(0, Kd);
-        __syncthreads();                 // the previous tile's readers are done with LDS
-        la.store(sA(0));
-        lb.store(sB(0));
-        __syncthreads();
-        for (int kt = 0; kt < nk; ++kt) {
-            const int cur = kt & 1;
-            if (kt + 1 < nk) {
-                la.load((kt + 1) * BK);
-                lb.load((kt + 1) * BK, Kd);
-            }
-            mma_step<WAVES_M, WAVES_N, WM, WN>(sA(cur), sB(cur), acc);
-            if (kt + 1 < nk) {
-                la.store(sA(cur ^ 1));
-                lb.store(sB(cur ^ 1));
-            }
-            __syncthreads();
-        }
+        k_loop<WAVES_M, WAVES_N, WM, WN>(
+            nk, smem, acc,
+            [&](int kt) { la.load(kt * BK); lb.load(kt * BK, Kd); },
+            [&](char* a, char* b) { la.store(a); lb.store(b); });
 
         // epilogue
         const int col_in = acc_col();
-#pragma unroll
-        for (int mi = 0; mi < WM; ++mi) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
+        static_for<WM>([&](auto mi) {
+            static_for<16>([&](auto r) {
                 const int m = (wm * WM + mi) * 32 + acc_row(r);
-                if (m >= te.rows) continue;
-                const size_t row = (size_t)te.row0 + m;
-                if (EPI == 0) {
-#pragma unroll
-                    for (int pi = 0; pi < WN / 2; ++pi) {
-                        const int col = n0 + (wn * (WN / 2) + pi) * 32 + col_in;
-                        if (col >= N) continue;
-                        const float a = acc[mi][2 * pi][r], b = acc[mi][2 * pi + 1][r];
-                        if (act != nullptr) {
-                            act[row * (size_t)(2 * N) + col] = float_to_bf16_bits(a);
-                            act[row * (size_t)(2 * N) + N + col] = float_to_bf16_bits(b);
-                        }
-                        C[row * (size_t)ldc + col] = float_to_bf16_bits(silu_mul(a, b));
-                    }
-                } else {
-#pragma unroll
-                    for (int ni = 0; ni < WN; ++ni) {
-                        const int col = n0 + (wn * WN + ni) * 32 + col_in;
-                        if (col >= N) continue;
-                        C[row * (size_t)ldc + col] = float_to_bf16_bits(acc[mi][ni][r]);
+                if (m < te.rows) {
+                    const size_t row = (size_t)te.row0 + m;
+                    if constexpr (EPI == 0) {
+                        static_for<WN / 2>([&](auto pi) {
+                            const int col = n0 + (wn * (WN / 2) + pi) * 32 + col_in;
+                            if (col < N) {
+                                const float a = acc[mi.value][2 * pi.value][r.value], b = acc[mi.value][2 * pi.value + 1][r.value];
+                                if (act != nullptr) {
+                                    act[row * (size_t)(2 * N) + col] = float_to_bf16_bits(a);
+                                    act[row * (size_t)(2 * N) + N + col] = float_to_bf16_bits(b);
+                                }
+                                C[row * (size_t)ldc + col] = float_to_bf16_bits(silu_mul(a, b));
+                            }
+                        });
+                    } else {
+                        static_for<WN>([&](auto ni) {
+                            const int col = n0 + (wn * WN + ni) * 32 + col_in;
+                            if (col < N) C[row * (size_t)ldc + col] = float_to_bf16_bits(acc[mi.value][ni.value][r.value]);
+                        });
                     }
                 }
-            }
-        }
+            });
+        });
     }
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, const void* wg, const void* wu,
-            const void* wd, const int32_t* seg_off, void* y_perm, void* act_save, char* ws, hipStream_t st) {
+            const void* wd, const int32_t* seg_off, void* h_buf, void* y_perm, void* act_save, TileEntry* tiles,
+            int32_t* count, int max_tiles, bool gemm1, bool gemm2, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
-    const FfnWs L = ffn_ws_layout(s);
-    auto* tiles = reinterpret_cast<TileEntry*>(ws + L.tiles);
-    auto* count = reinterpret_cast<int32_t*>(ws + L.count);
-    auto* h = reinterpret_cast<uint16_t*>(ws + L.h);
-    FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, L.max_tiles, st));
+    auto* h = reinterpret_cast<uint16_t*>(h_buf);
+    FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
     const size_t lds = (size_t)2 * (BM + BN) * 128;
     auto k1 = k_ffn_gemm<WAVES_M, WAVES_N, WM, WN, 0>;
     auto k2 = k_ffn_gemm<WAVES_M, WAVES_N, WM, WN, 1>;
@@ -142,34 +113,54 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     }
     const int blocks_per_cu = (lds <= 80 * 1024) ? 2 : 1;
     const int grid = 256 * blocks_per_cu;
-    if (!(s.flags & FINE_FLAG_ONLY_GEMM2))
-    hipLaunchKernelGGL(k1, dim3(grid), dim3(256), lds, st, (const uint16_t*)x_perm, s.d, (const uint16_t*)wg,
-                       (const uint16_t*)wu, (size_t)s.d * s.f, s.d, s.f, h, s.f, (uint16_t*)act_save, tiles, count);
-    FINE_LAUNCH_CHECK();
-    if (!(s.flags & FINE_FLAG_ONLY_GEMM1))
-    hipLaunchKernelGGL(k2, dim3(grid), dim3(256), lds, st, (const uint16_t*)h, s.f, (const uint16_t*)wd,
-                       (const uint16_t*)nullptr, (size_t)s.f * s.d, s.f, s.d, (uint16_t*)y_perm, s.d,
-                       (uint16_t*)nullptr, tiles, count);
-    FINE_LAUNCH_CHECK();
+    if (gemm1) {
+        hipLaunchKernelGGL(k1, dim3(grid), dim3(256), lds, st, (const uint16_t*)x_perm, s.d, (const uint16_t*)wg,
+                           (const uint16_t*)wu, (size_t)s.d * s.f, s.d, s.f, h, s.f, (uint16_t*)act_save, tiles, count);
+        FINE_LAUNCH_CHECK();
+    }
+    if (gemm2) {
+        hipLaunchKernelGGL(k2, dim3(grid), dim3(256), lds, st, (const uint16_t*)h, s.f, (const uint16_t*)wd,
+                           (const uint16_t*)nullptr, (size_t)s.f * s.d, s.f, s.d, (uint16_t*)y_perm, s.d,
+                           (uint16_t*)nullptr, tiles, count);
+        FINE_LAUNCH_CHECK();
+    }
     return FINE_OK;
 }
 
-}  // namespace
-
-int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm,
-                    const void* wg, const void* wu, const void* wd, const int32_t* seg_off,
-                    void* y_perm, void* act_save, char* ws, hipStream_t st) {
+int pick_tile(const fine_shape& s) {
     // expected rows of a (rank, expert) segment when every expert is on every rank: a
     // rank's ceil(P/G) rows span about E/G + 1 experts
     const double P = (double)s.T * s.K;
     const double seg_rows = (P / s.G) / ((double)s.E / s.G + 1.0);
     int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
     if (tile == 0) tile = seg_rows >= 384.0 ? 3 : (seg_rows >= 96.0 ? 2 : 1);
+    return tile;
+}
+
+}  // namespace
+
+int launch_ffn_parts(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, const void* wg,
+                     const void* wu, const void* wd, const int32_t* seg_off, void* h_buf, void* y_perm,
+                     void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, bool gemm1, bool gemm2,
+                     hipStream_t st) {
+    const int tile = pick_tile(s);
     if (tile == 3)
-        return run_ffn<2, 2, 4, 4>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, y_perm, act_save, ws, st);
+        return run_ffn<2, 2, 4, 4>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles,
+                                   count, max_tiles, gemm1, gemm2, st);
     if (tile == 2)
-        return run_ffn<2, 2, 2, 4>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, y_perm, act_save, ws, st);
-    return run_ffn<1, 4, 2, 2>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, y_perm, act_save, ws, st);
+        return run_ffn<2, 2, 2, 4>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles,
+                                   count, max_tiles, gemm1, gemm2, st);
+    return run_ffn<1, 4, 2, 2>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles, count,
+                               max_tiles, gemm1, gemm2, st);
+}
+
+int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm,
+                    const void* wg, const void* wu, const void* wd, const int32_t* seg_off,
+                    void* y_perm, void* act_save, char* ws, hipStream_t st) {
+    const FfnWs L = ffn_ws_layout(s);
+    return launch_ffn_parts(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, ws + L.h, y_perm, act_save,
+                            reinterpret_cast<TileEntry*>(ws + L.tiles), reinterpret_cast<int32_t*>(ws + L.count),
+                            L.max_tiles, !(s.flags & FINE_FLAG_ONLY_GEMM2), !(s.flags & FINE_FLAG_ONLY_GEMM1), st);
 }
 
 }  // namespace fine

@@ -16,6 +16,8 @@
 // of step i and written to the other LDS buffer afterwards; one barrier per step.
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace fine {
@@ -27,6 +29,20 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;           // k-values per LDS tile row (128 bytes)
 constexpr int kThreads = 256;
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), so that
+// accumulator registers are only ever indexed by constants.
+template <int I, int N, typename F>
+__device__ inline void static_for_impl(F& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for_impl<I + 1, N>(f);
+    }
+}
+template <int N, typename F>
+__device__ inline void static_for(F f) { static_for_impl<0, N>(f); }
+
+__device__ inline int cdiv_dev(int a, int b) { return (a + b - 1) / b; }
 
 __device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
 
@@ -46,7 +62,7 @@ struct LoaderKC {
 #pragma unroll
         for (int i = 0; i < N; ++i) ptr[i] = row_ptr((tid >> 3) + 32 * i) + (tid & 7) * 8;
     }
-    __device__ inline void load(int k0) {
+    __device__ inline void load(ptrdiff_t k0) {
 #pragma unroll
         for (int i = 0; i < N; ++i) reg[i] = *reinterpret_cast<const u32x4*>(ptr[i] + k0);
     }
@@ -136,6 +152,34 @@ __device__ inline void mma_step(const char* sA, const char* sB, f32x16 (&acc)[WM
             for (int ni = 0; ni < WN; ++ni)
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
     }
+}
+
+// The double-buffered k-loop shared by every grouped GEMM.  load(kt) brings k-tile kt from
+// global memory into the loaders' registers, store(sA, sB) writes those registers into one
+// LDS buffer pair.  On return every wave has finished reading LDS.
+template <int WAVES_M, int WAVES_N, int WM, int WN, typename Load, typename Store>
+__device__ inline void k_loop(int nk, char* smem, f32x16 (&acc)[WM][WN], Load load, Store store) {
+    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    auto sA = [&](int buf) { return smem + buf * (BM * 128); };
+    auto sB = [&](int buf) { return smem + 2 * BM * 128 + buf * (BN * 128); };
+    if (nk <= 0) return;
+    load(0);
+    store(sA(0), sB(0));
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) load(kt + 1);
+        mma_step<WAVES_M, WAVES_N, WM, WN>(sA(cur), sB(cur), acc);
+        if (kt + 1 < nk) store(sA(cur ^ 1), sB(cur ^ 1));
+        __syncthreads();
+    }
+}
+
+// Blocks are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the
+// work list so that blocks sharing an L2 also share operand tiles.
+__device__ inline int xcd_contiguous_id() {
+    const int b = blockIdx.x, n = gridDim.x;
+    return (n % 8 == 0) ? (b % 8) * (n / 8) + b / 8 : b;
 }
 
 // Row and column (inside the 32x32 MFMA tile) of accumulator register r of this lane.

@@ -1,0 +1,120 @@
+"""GPU parity of the backward pass against the oracle's closed-form gradients."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_16947_amd as fm
+import workloads as wl
+from oracle import moe
+from gpu_common import GpuLayer, check_schedule_against_oracle, max_rel_err, to64, weights_of_factory
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+TOL = 2e-2
+
+
+class GpuBackward:
+    def __init__(self, layer: GpuLayer):
+        s, dev = layer.shape, layer.inp.x.device
+        self.layer = layer
+        self.ws = fm.alloc_workspace(s, fm.WS_BACKWARD, dev)
+        self.d_x = torch.full((s.T, s.d), float("nan"), dtype=s.torch_dtype, device=dev)
+        self.d_topk_w = torch.full((s.T, s.K), float("nan"), dtype=torch.float32, device=dev)
+        self.d_wg = torch.full((s.E, s.d, s.f), float("nan"), dtype=torch.float32, device=dev)
+        self.d_wu = torch.full((s.E, s.d, s.f), float("nan"), dtype=torch.float32, device=dev)
+        self.d_wd = torch.full((s.E, s.f, s.d), float("nan"), dtype=torch.float32, device=dev)
+
+    def run(self, accumulate=False):
+        L, i = self.layer, self.layer.inp
+        fm.fine_backward(L.shape, -1, i.d_out, L.x_perm, L.y_perm, L.act_save, i.w_gate, i.w_up, i.w_down,
+                         L.sb.row_of_pair, L.sb.pair_of_row, L.sb.seg_off, L.topk_w, self.d_x, self.d_topk_w,
+                         self.d_wg, self.d_wu, self.d_wd, accumulate, self.ws)
+        torch.cuda.synchronize()
+
+
+def small_train_cfgs():
+    c5 = wl.CONFIGS["cfg5_train"]
+    return [
+        wl.scaled(c5, name="cfg5_small", T=2048, d=128, f=256),
+        wl.scaled(c5, name="cfg5_ragged", T=1024, d=192, f=320, E=16, K=2, G=4, bias_kind="scaled_z", bias_scale=1.5),
+        wl.scaled(c5, name="cfg5_topk4", T=512, d=256, f=128, E=32, K=4, G=8, bias_kind="scaled_z", bias_scale=2.0),
+    ]
+
+
+@pytest.mark.parametrize("cfg", small_train_cfgs(), ids=lambda c: c.name)
+@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("saved", [False, True])
+def test_backward_elementwise(cfg, tile, saved):
+    print("backward case", cfg.name, "tile", tile, "act_save", saved, flush=True)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+    if saved:
+        layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+    layer.forward()
+    bwd = GpuBackward(layer)
+    bwd.run()
+
+    idx = layer.topk_idx.cpu().numpy()
+    w = to64(layer.topk_w)
+    check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G)
+    g = moe.backward_dense(to64(inp.x), idx, w, weights_of_factory(inp), to64(inp.d_out))
+    assert max_rel_err(to64(bwd.d_x), g["d_x"]) <= TOL
+    assert max_rel_err(to64(bwd.d_topk_w), g["d_topk_w"]) <= TOL
+    for e in range(cfg.E):
+        for got, key in ((bwd.d_wg, "d_w_gate"), (bwd.d_wu, "d_w_up"), (bwd.d_wd, "d_w_down")):
+            if e in g[key]:
+                assert max_rel_err(to64(got[e]), g[key][e]) <= TOL, (key, e)
+            else:
+                assert not got[e].any(), (key, e)          # experts without tokens: exact zeros
+
+    if tile == 0 and not saved:
+        # accumulate adds to what is there
+        before = bwd.d_wd.clone()
+        bwd.run(accumulate=True)
+        assert max_rel_err(to64(bwd.d_wd), 2.0 * to64(before)) <= 1e-6
+
+
+def test_backward_full_size_cfg5_sampled():
+    cfg = wl.CONFIGS["cfg5_train"]
+    print("full-size backward cfg5", flush=True)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp)
+    layer.forward(per_rank=True)
+    bwd = GpuBackward(layer)
+    bwd.run()
+    print("  backward done", flush=True)
+    idx = layer.topk_idx.cpu().numpy()
+    w = to64(layer.topk_w)
+    want = check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G)
+    assert not torch.isnan(bwd.d_x.float()).any() and not torch.isnan(bwd.d_topk_w).any()
+    assert not torch.isnan(bwd.d_wg).any() and not torch.isnan(bwd.d_wu).any() and not torch.isnan(bwd.d_wd).any()
+    weights_of = weights_of_factory(inp)
+
+    # d_x and d_topk_w on sampled tokens (a token's gradients depend on its own pairs only)
+    rng = np.random.default_rng(7)
+    tokens = np.unique(np.concatenate([rng.choice(cfg.T, size=24, replace=False), [0, cfg.T - 1]]))
+    tt = torch.from_numpy(tokens).to(DEV)
+    g = moe.backward_dense(to64(inp.x[tt]), idx[tokens], w[tokens], weights_of, to64(inp.d_out[tt]),
+                           want_weight_grads=False)
+    assert max_rel_err(to64(bwd.d_x[tt]), g["d_x"]) <= TOL
+    assert max_rel_err(to64(bwd.d_topk_w[tt]), g["d_topk_w"]) <= TOL
+    print("  sampled d_x, d_topk_w ok", flush=True)
+
+    # weight gradients: sampled columns of the hottest expert (its rows are split over many
+    # ranks) and of one ordinary expert
+    load = want["load"]
+    hot = int(np.argmax(load))
+    cold = int(np.argsort(load)[len(load) // 2])
+    for e in (hot, cold):
+        t_e, k_e = np.nonzero(idx == e)
+        te = torch.from_numpy(t_e).to(DEV)
+        x_rows = to64(inp.x[te])
+        dy_rows = w[t_e, k_e][:, None] * to64(inp.d_out[te])
+        cols = [0, 77, cfg.f - 1]
+        ref = moe.weight_grad_columns(x_rows, dy_rows, *weights_of(e), cols=cols)
+        for j in cols:
+            cg, cu, cd = ref[j]
+            assert max_rel_err(to64(bwd.d_wg[e, :, j]), cg) <= TOL, (e, j)
+            assert max_rel_err(to64(bwd.d_wu[e, :, j]), cu) <= TOL, (e, j)
+            assert max_rel_err(to64(bwd.d_wd[e, j, :]), cd) <= TOL, (e, j)
+        print("  expert %d (%d rows) weight-gradient columns ok" % (e, len(t_e)), flush=True)

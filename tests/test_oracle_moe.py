@@ -126,3 +126,16 @@ def test_workload_generator_shapes_and_determinism():
     i5 = wl.make_inputs(c5)
     assert i5.bias[0] == 4.0 and not i5.bias[1:].any() and i5.d_out.shape == (64, 32)
     assert i5.x.dtype == torch.bfloat16
+
+
+def test_weight_grad_columns_match_the_full_gradients():
+    x, W, idx, w = tiny_layer(seed=5, T=20, d=6, f=9, E=3, K=2)
+    d_out = np.random.default_rng(1).standard_normal(x.shape)
+    g = moe.backward_dense(x, idx, w, lambda e: W[e], d_out)
+    for e in g["d_w_gate"]:
+        tt, kk = np.nonzero(idx == e)
+        cols = moe.weight_grad_columns(x[tt], w[tt, kk][:, None] * d_out[tt], *W[e], cols=[0, 4, 8])
+        for j, (cg, cu, cd) in cols.items():
+            assert np.allclose(cg, g["d_w_gate"][e][:, j], rtol=1e-12, atol=1e-14)
+            assert np.allclose(cu, g["d_w_up"][e][:, j], rtol=1e-12, atol=1e-14)
+            assert np.allclose(cd, g["d_w_down"][e][j, :], rtol=1e-12, atol=1e-14)
