@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--detail-iters", type=int, default=10)
+    ap.add_argument("--also-fused", action="store_true", help="also time one fine_grouped_ffn call for all ranks")
     return ap.parse_args()
 
 
@@ -134,7 +135,7 @@ def main():
 
     it = args.detail_iters
     stage_ms = {name: float(np.median(time_ms(fn, it))) for name, fn in stages}
-    if args.ffn == "per_rank":
+    if args.ffn == "per_rank" and args.also_fused:
         stage_ms["ffn_fused_call"] = float(np.median(time_ms(lambda: st_ffn_rank(-1), it)))
     rank_ms = [float(np.median(time_ms(lambda r=r: st_ffn_rank(r), it))) for r in range(s.G)]
     rank_rows = np.diff(sb.rank_off.cpu().numpy()).astype(np.int64)

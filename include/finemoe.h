@@ -108,9 +108,10 @@ int fine_topk(const fine_shape* shape, const void* x, const void* w_router, cons
  *   rank_off [G+1]  first row of each rank; rank_off[G] = P
  * With place == NULL the replica loads have a closed form (cut the expert-sorted pair
  * sequence into chunks of M* = ceil(P/G)); with a placement the optimum is found by
- * exact integer max-flows on the device.  Returns FINE_INFEASIBLE only for what the host
- * can see (it cannot read `place`): an expert whose row of `place` is empty receives no
- * replica and its pairs are reported by max_load[0] = -1.
+ * exact integer augmenting paths on the device (limit: E*G*4 + E*8 + G*G*4 bytes must fit
+ * in 160 KB of LDS, else FINE_UNSUPPORTED).  The host cannot read `place`: if an expert with
+ * load has an empty row of `place` no schedule exists; then max_load[0] = -1, x_eg = 0 and
+ * pair_dst = row_of_pair = -1 for every pair (pair_of_row is left untouched).
  */
 int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
                int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
@@ -148,14 +149,15 @@ int fine_combine(const fine_shape* shape, const void* y_perm, const int32_t* row
                  const float* topk_w, void* out, void* stream);
 
 /*
- * Backward of permute + expert computation + combine for rank `rank` (-1 = all ranks in
- * ascending order).  The paper aggregates the gradients of an expert's replicas with a
- * data-parallel all-reduce (Section 2.2); on one GPU the replicas share one fp32
- * accumulator per expert, added in ascending rank order.
- *   d_out [T,d] dtype; x_perm, y_perm [P,d]; act_save [P,2f] or NULL (then recomputed);
- *   d_x [T,d] dtype out (rank == -1 only; per-rank calls leave it untouched and fill the
- *        rank's rows of the internal d_x_perm, see DESIGN notes in the Python binding);
- *   d_topk_w [T,K] fp32 out: <d_out[t], y_perm[row]> (entries of other ranks untouched);
+ * Backward of permute + expert computation + combine for all ranks (rank must be -1;
+ * other values return FINE_UNSUPPORTED), FINE_BF16 only.  The paper aggregates the
+ * gradients of an expert's replicas with a data-parallel all-reduce (Section 2.2); on one
+ * GPU the replicas share one fp32 accumulator per expert, summed in ascending rank order.
+ *   d_out [T,d] dtype; x_perm, y_perm [P,d] as produced by the forward entry points;
+ *   act_save [P,2f] as written by fine_grouped_ffn, or NULL (then recomputed into ws);
+ *   d_x [T,d] dtype out: d_x[t] = sum_k dXp[row_of_pair[t*K+k]];
+ *   d_topk_w [T,K] fp32 out: <d_out[t], y_perm[row_of_pair[t*K+k]]> (the router itself is
+ *        not differentiated);
  *   d_w_gate, d_w_up [E,d,f] fp32, d_w_down [E,f,d] fp32: accumulate != 0 adds to the
  *        buffers, accumulate == 0 overwrites them (experts without rows get zeros).
  */

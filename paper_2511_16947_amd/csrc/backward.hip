@@ -36,30 +36,41 @@ __global__ __launch_bounds__(256) void k_bwd_dh(const uint16_t* __restrict__ dy,
         lb.init([&](int n) { return W + (size_t)min(n0 + n, f - 1) * d; });
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
-        k_loop<WAVES_M, WAVES_N, WM, WN>(
-            d / BK, smem, acc, [&](int kt) { la.load(kt * BK); lb.load(kt * BK); },
-            [&](char* a, char* b) { la.store(a); lb.store(b); });
-        const int col_in = acc_col();
-        static_for<WM>([&](auto mi) {
-            static_for<16>([&](auto r) {
-                const int m = (wm * WM + mi) * 32 + acc_row(r);
-                if (m < te.rows) {
-                    const size_t row = (size_t)te.row0 + m;
-                    static_for<WN>([&](auto ni) {
-                        const int col = n0 + (wn * WN + ni) * 32 + col_in;
-                        if (col < f) {
-                            const float dh = acc[mi.value][ni.value][r.value];
-                            const float a = bf16_bits_to_float(act[row * (size_t)(2 * f) + col]);
-                            const float b = bf16_bits_to_float(act[row * (size_t)(2 * f) + f + col]);
-                            const float s = 1.f / (1.f + __expf(-a));
-                            dact[row * (size_t)(2 * f) + col] = float_to_bf16_bits(dh * b * s * (1.f + a * (1.f - s)));
-                            dact[row * (size_t)(2 * f) + f + col] = float_to_bf16_bits(dh * a * s);
-                            h[row * (size_t)f + col] = float_to_bf16_bits(a * s * b);
-                        }
-                    });
-                }
-            });
+        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(d / BK, smem, acc, la, lb, [&](int kt) {
+            return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)kt * BK, 0};
         });
+        constexpr int WMC = (BM * (BN * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
+        stage_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(
+            smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
+            [&](int m, int c, uint2 dh4) {
+                const int col = n0 + c;
+                if (m >= te.rows || col >= f) return;
+                const size_t row = (size_t)te.row0 + m;
+                const uint2 a4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + col);
+                const uint2 b4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + f + col);
+                const uint32_t dhw[2] = {dh4.x, dh4.y}, aw[2] = {a4.x, a4.y}, bw[2] = {b4.x, b4.y};
+                uint32_t da[2], db[2], hh[2];
+#pragma unroll
+                for (int w = 0; w < 2; ++w) {
+                    float o_da[2], o_db[2], o_h[2];
+#pragma unroll
+                    for (int hlf = 0; hlf < 2; ++hlf) {
+                        const float dh = bf16_bits_to_float((uint16_t)(dhw[w] >> (16 * hlf)));
+                        const float a = bf16_bits_to_float((uint16_t)(aw[w] >> (16 * hlf)));
+                        const float b = bf16_bits_to_float((uint16_t)(bw[w] >> (16 * hlf)));
+                        const float sg = 1.f / (1.f + __expf(-a));
+                        o_da[hlf] = dh * b * sg * (1.f + a * (1.f - sg));
+                        o_db[hlf] = dh * a * sg;
+                        o_h[hlf] = a * sg * b;
+                    }
+                    da[w] = pack_bf16x2(o_da[0], o_da[1]);
+                    db[w] = pack_bf16x2(o_db[0], o_db[1]);
+                    hh[w] = pack_bf16x2(o_h[0], o_h[1]);
+                }
+                *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + col) = make_uint2(da[0], da[1]);
+                *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + f + col) = make_uint2(db[0], db[1]);
+                *reinterpret_cast<uint2*>(h + row * (size_t)f + col) = make_uint2(hh[0], hh[1]);
+            });
     }
 }
 
@@ -86,26 +97,13 @@ __global__ __launch_bounds__(256) void k_bwd_dx(const uint16_t* __restrict__ dac
         const ptrdiff_t to_up = Wu - Wg;
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
-        k_loop<WAVES_M, WAVES_N, WM, WN>(
-            2 * nkf, smem, acc,
-            [&](int kt) {
-                la.load(kt * BK);
-                lb.load(kt < nkf ? (ptrdiff_t)kt * BK : to_up + (ptrdiff_t)(kt - nkf) * BK);
-            },
-            [&](char* a, char* b) { la.store(a); lb.store(b); });
-        const int col_in = acc_col();
-        static_for<WM>([&](auto mi) {
-            static_for<16>([&](auto r) {
-                const int m = (wm * WM + mi) * 32 + acc_row(r);
-                if (m < te.rows) {
-                    const size_t row = (size_t)te.row0 + m;
-                    static_for<WN>([&](auto ni) {
-                        const int col = n0 + (wn * WN + ni) * 32 + col_in;
-                        if (col < d) dxp[row * (size_t)d + col] = float_to_bf16_bits(acc[mi.value][ni.value][r.value]);
-                    });
-                }
-            });
+        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(2 * nkf, smem, acc, la, lb, [&](int kt) {
+            return KTile{(ptrdiff_t)kt * BK, kt < nkf ? (ptrdiff_t)kt * BK : to_up + (ptrdiff_t)(kt - nkf) * BK, 0};
         });
+        constexpr int WMC = (BM * (BN * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
+        store_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(
+            smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
+            dxp, (size_t)d, te.row0, te.rows, n0, d);
     }
 }
 
@@ -135,9 +133,9 @@ __global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1,
         else if (j >= t0) { p = p1; j -= t0; }
         const int ntm = cdiv_dev(p.M, BM);
         const int m0 = (j % ntm) * BM, n0 = (j / ntm) * BN;
-        LoaderMC<BM> la;
+        LoaderMC<BM, true> la;
         la.init([&](int r8) { return p.A + min(m0 + 8 * r8, p.M - 8); }, (size_t)p.lda);
-        LoaderMC<BN> lb;
+        LoaderMC<BN, true> lb;
         lb.init([&](int r8) { return p.B + min(n0 + 8 * r8, p.N - 8); }, (size_t)p.ldb);
         // k-tiles: 64 rows at a time through the expert's segment on every rank, ascending
         int nk = 0;
@@ -146,34 +144,37 @@ __global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1,
         int cur_g = -1, cur_k = 0, cur_hi = 0;
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
-        k_loop<WAVES_M, WAVES_N, WM, WN>(
-            nk, smem, acc,
-            [&](int) {
-                while (cur_k >= cur_hi) {          // advance to the next non-empty segment
-                    ++cur_g;
-                    cur_k = seg_off[(size_t)cur_g * (E + 1) + e];
-                    cur_hi = seg_off[(size_t)cur_g * (E + 1) + e + 1];
-                }
-                la.load(cur_k, cur_hi);
-                lb.load(cur_k, cur_hi);
-                cur_k += BK;
-            },
-            [&](char* a, char* b) { la.store(a); lb.store(b); });
+        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, [&](int) {
+            while (cur_k >= cur_hi) {          // advance to the next non-empty segment
+                ++cur_g;
+                cur_k = seg_off[(size_t)cur_g * (E + 1) + e];
+                cur_hi = seg_off[(size_t)cur_g * (E + 1) + e + 1];
+            }
+            const KTile t{(ptrdiff_t)cur_k, (ptrdiff_t)cur_k, cur_hi};
+            cur_k += BK;
+            return t;
+        });
         float* out = p.out + (size_t)e * p.M * p.N;
-        const int col_in = acc_col();
+        // each lane owns four consecutive columns of a row: 16-byte stores
         static_for<WM>([&](auto mi) {
-            static_for<16>([&](auto r) {
-                const int m = m0 + (wm * WM + mi) * 32 + acc_row(r);
-                if (m < p.M) {
-                    static_for<WN>([&](auto ni) {
-                        const int col = n0 + (wn * WN + ni) * 32 + col_in;
+            const int m = m0 + (wm * WM + mi.value) * 32 + acc_m();
+            if (m < p.M) {
+                static_for<WN>([&](auto ni) {
+                    static_for<4>([&](auto rg) {
+                        const int col = n0 + (wn * WN + ni.value) * 32 + acc_n(rg.value);
                         if (col < p.N) {
-                            float* dst = out + (size_t)m * p.N + col;
-                            *dst = accumulate ? *dst + acc[mi.value][ni.value][r.value] : acc[mi.value][ni.value][r.value];
+                            float4* dst = reinterpret_cast<float4*>(out + (size_t)m * p.N + col);
+                            float4 v = make_float4(acc[mi.value][ni.value][4 * rg.value], acc[mi.value][ni.value][4 * rg.value + 1],
+                                                   acc[mi.value][ni.value][4 * rg.value + 2], acc[mi.value][ni.value][4 * rg.value + 3]);
+                            if (accumulate) {
+                                const float4 o = *dst;
+                                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                            }
+                            *dst = v;
                         }
                     });
-                }
-            });
+                });
+            }
         });
     }
 }

@@ -42,9 +42,15 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
         const uint16_t* Bg = B0 + (size_t)te.expert * b_expert_stride;
         const uint16_t* Bu = (EPI == 0) ? B1 + (size_t)te.expert * b_expert_stride : nullptr;
 
+#ifdef FINE_PROFILE_LOOP
+#define FINE_PROF_TILE(slot) do { if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + (slot)] = clock64(); } while (0)
+#else
+#define FINE_PROF_TILE(slot) do { } while (0)
+#endif
+        FINE_PROF_TILE(0);
         LoaderKC<BM> la;
         la.init([&](int r) { return A + (size_t)(te.row0 + min(r, te.rows - 1)) * lda; });
-        LoaderMC<BN> lb;
+        LoaderMC<BN, false> lb;
         lb.init([&](int r8) {
             const int nb = r8 * 8;
             if (EPI == 0) {
@@ -59,39 +65,36 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
 
-        k_loop<WAVES_M, WAVES_N, WM, WN>(
-            nk, smem, acc,
-            [&](int kt) { la.load(kt * BK); lb.load(kt * BK, Kd); },
-            [&](char* a, char* b) { la.store(a); lb.store(b); });
-
-        // epilogue
-        const int col_in = acc_col();
-        static_for<WM>([&](auto mi) {
-            static_for<16>([&](auto r) {
-                const int m = (wm * WM + mi) * 32 + acc_row(r);
-                if (m < te.rows) {
-                    const size_t row = (size_t)te.row0 + m;
-                    if constexpr (EPI == 0) {
-                        static_for<WN / 2>([&](auto pi) {
-                            const int col = n0 + (wn * (WN / 2) + pi) * 32 + col_in;
-                            if (col < N) {
-                                const float a = acc[mi.value][2 * pi.value][r.value], b = acc[mi.value][2 * pi.value + 1][r.value];
-                                if (act != nullptr) {
-                                    act[row * (size_t)(2 * N) + col] = float_to_bf16_bits(a);
-                                    act[row * (size_t)(2 * N) + N + col] = float_to_bf16_bits(b);
-                                }
-                                C[row * (size_t)ldc + col] = float_to_bf16_bits(silu_mul(a, b));
-                            }
-                        });
-                    } else {
-                        static_for<WN>([&](auto ni) {
-                            const int col = n0 + (wn * WN + ni) * 32 + col_in;
-                            if (col < N) C[row * (size_t)ldc + col] = float_to_bf16_bits(acc[mi.value][ni.value][r.value]);
-                        });
-                    }
-                }
-            });
+        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, [&](int kt) {
+            return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)kt * BK, Kd};
         });
+
+        // epilogue: LDS-staged, 8-byte coalesced stores
+        FINE_PROF_TILE(1);
+        if constexpr (EPI == 0) {
+            constexpr int WMC = (BM * (BNC * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
+            if (act != nullptr) {
+                store_tile_bf16<WAVES_M, WAVES_N, WM, WN / 2, WMC>(
+                    smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][2 * t.value][4 * rg.value + q.value]; },
+                    act, (size_t)(2 * N), te.row0, te.rows, n0, N);
+                store_tile_bf16<WAVES_M, WAVES_N, WM, WN / 2, WMC>(
+                    smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][2 * t.value + 1][4 * rg.value + q.value]; },
+                    act + N, (size_t)(2 * N), te.row0, te.rows, n0, N);
+            }
+            store_tile_bf16<WAVES_M, WAVES_N, WM, WN / 2, WMC>(
+                smem,
+                [&](auto mi, auto t, auto rg, auto q) {
+                    return silu_mul(acc[mi.value][2 * t.value][4 * rg.value + q.value],
+                                    acc[mi.value][2 * t.value + 1][4 * rg.value + q.value]);
+                },
+                C, (size_t)ldc, te.row0, te.rows, n0, N);
+        } else {
+            constexpr int WMC = (BM * (BNC * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
+            store_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(
+                smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
+                C, (size_t)ldc, te.row0, te.rows, n0, N);
+        }
+        FINE_PROF_TILE(2);
     }
 }
 
@@ -164,3 +167,9 @@ int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x
 }
 
 }  // namespace fine
+
+#ifdef FINE_PROFILE_LOOP
+extern "C" __attribute__((visibility("default"))) int fine_debug_prof(unsigned long long* host_out) {
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(fine::mfma::g_prof), sizeof(unsigned long long) * 128 * 8);
+}
+#endif

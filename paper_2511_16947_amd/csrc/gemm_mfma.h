@@ -12,8 +12,8 @@
 //             forward pass, both operands of the weight gradients): each thread loads an
 //             8(k) x 8(row) block, transposes it in registers with byte permutes and
 //             writes eight 16-byte chunks.
-// The k-loop is double buffered: global loads for step i+1 are issued before the MFMAs
-// of step i and written to the other LDS buffer afterwards; one barrier per step.
+// The k-loop is double buffered (registers -> other LDS buffer, one barrier per step) and
+// its instruction order is fixed by hand, see k_step().
 #pragma once
 
 #include <type_traits>
@@ -30,12 +30,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int BK = 64;           // k-values per LDS tile row (128 bytes)
 constexpr int kThreads = 256;
 
+template <int I> using IntC = std::integral_constant<int, I>;
+
 // Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), so that
 // accumulator registers are only ever indexed by constants.
 template <int I, int N, typename F>
 __device__ inline void static_for_impl(F& f) {
     if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
+        f(IntC<I>{});
         static_for_impl<I + 1, N>(f);
     }
 }
@@ -44,17 +46,26 @@ __device__ inline void static_for(F f) { static_for_impl<0, N>(f); }
 
 __device__ inline int cdiv_dev(int a, int b) { return (a + b - 1) / b; }
 
-__device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
+__device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^ ((row >> 1) & 7)) << 4); }
+
+// Where k-tile kt starts in the two sources (elements for LoaderKC, rows for LoaderMC) and
+// where the valid source rows end (ragged LoaderMC only).
+struct KTile {
+    ptrdiff_t a, b;
+    int end;
+};
 
 // ---------------------------------------------------------------------------
 // Source contiguous along k.  Thread (tid & 7) = 16-byte chunk of the 128-byte row
-// piece, (tid >> 3) + 32 i = tile row.
+// piece, (tid >> 3) + 32 i = tile row.  One global load and one LDS write per i.
 // ---------------------------------------------------------------------------
 template <int ROWS>
 struct LoaderKC {
     static constexpr int N = ROWS / 32;
+    static constexpr int kLoads = N, kStores = N;      // instructions per k-tile
+    static constexpr bool kPieceRecycle = true;        // a piece may be reloaded right after its write
     const uint16_t* ptr[N];
-    u32x4 reg[N];
+    u32x4 reg[2][N];
     // row_ptr(r) returns the address of element k = 0 of tile row r
     template <typename RowPtr>
     __device__ inline void init(RowPtr row_ptr) {
@@ -62,129 +73,134 @@ struct LoaderKC {
 #pragma unroll
         for (int i = 0; i < N; ++i) ptr[i] = row_ptr((tid >> 3) + 32 * i) + (tid & 7) * 8;
     }
-    __device__ inline void load(ptrdiff_t k0) {
-#pragma unroll
-        for (int i = 0; i < N; ++i) reg[i] = *reinterpret_cast<const u32x4*>(ptr[i] + k0);
+    template <int I, int SET>
+    __device__ inline void load_one(ptrdiff_t k0, int /*k_end*/) {
+        reg[SET][I] = *reinterpret_cast<const u32x4*>(ptr[I] + k0);
     }
-    __device__ inline void store(char* lds) const {
+    template <int I, int SET>
+    __device__ inline void store_one(char* lds) const {
         const int tid = threadIdx.x;
-#pragma unroll
-        for (int i = 0; i < N; ++i)
-            *reinterpret_cast<u32x4*>(lds + lds_off((tid >> 3) + 32 * i, tid & 7)) = reg[i];
+        *reinterpret_cast<u32x4*>(lds + lds_off((tid >> 3) + 32 * I, tid & 7)) = reg[SET][I];
     }
 };
 
 // ---------------------------------------------------------------------------
 // Source contiguous along the tile row index r (element (k, r) at col_ptr(r) + k*ld).
-// Unit u = tid + 256 i: k-block (u & 7) of 8 k-values, row block (u >> 3) of 8 rows.
+// Thread t: k-block (t & 7) of 8 k-values, row block (t >> 3) of 8 rows (ROWS = 256), i.e.
+// eight 16-byte global loads (one per k) and, after an 8x8 transpose, eight LDS writes.
+// RAGGED: rows of the source at k >= k_end read as zero (contraction over ragged ranges);
+// the address is clamped to the last valid row, so there is no branch.
 // ---------------------------------------------------------------------------
-template <int ROWS>
+template <int ROWS, bool RAGGED>
 struct LoaderMC {
-    static constexpr int N = (ROWS + 255) / 256;
-    const uint16_t* ptr[N];
-    size_t ld;
-    u32x4 reg[N][8];
-    // col_ptr(r8) returns the address of element (k = 0, row = 8*r8) ; the 8 rows of a
-    // block must be contiguous in memory.
+    static_assert(ROWS == 256 || ROWS == 128, "tile rows");
+    static constexpr int kLoads = 8, kStores = 8;
+    static constexpr bool kPieceRecycle = false;       // every write needs all eight loads of its set
+    const uint16_t* ptr;
+    ptrdiff_t ld;
+    u32x4 reg[2][8];     // two sets: every LDS write needs all eight loads of its set, so one set
+                         // is drained while the other is being filled
+    // col_ptr(r8) returns the address of element (k = 0, row = 8*r8); the 8 rows of a block
+    // must be contiguous in memory.  For ROWS = 128 the upper half of the threads repeats
+    // the lower half's work (same addresses, same LDS cells, same values).
     template <typename ColPtr>
     __device__ inline void init(ColPtr col_ptr, size_t ld_) {
-        ld = ld_;
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int u = threadIdx.x + 256 * i;
-            ptr[i] = (u < ROWS) ? col_ptr(u >> 3) + (size_t)(u & 7) * 8 * ld : nullptr;
+        ld = (ptrdiff_t)ld_;
+        const int u = threadIdx.x % ROWS;
+        ptr = col_ptr(u >> 3) + (ptrdiff_t)(u & 7) * 8 * ld;
+    }
+    template <int J, int SET>
+    __device__ inline void load_one(ptrdiff_t k0, int k_end) {
+        if constexpr (RAGGED) {
+            const int kblock8 = (int)((threadIdx.x % ROWS) & 7) * 8;
+            const int k = (int)k0 + kblock8 + J;                  // absolute source row
+            const int kc = min(k, k_end - 1);                     // last valid row instead of a branch
+            const u32x4 v = *reinterpret_cast<const u32x4*>(ptr + (ptrdiff_t)(kc - kblock8) * ld);
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            reg[SET][J] = (k < k_end) ? v : z;
+        } else {
+            reg[SET][J] = *reinterpret_cast<const u32x4*>(ptr + (k0 + J) * ld);
         }
     }
-    // rows of the source at k >= k_end read as zero (ragged contraction ranges)
-    __device__ inline void load(int k0, int k_end) {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int u = threadIdx.x + 256 * i;
-            if (u < ROWS) {
-                const int kb = k0 + (u & 7) * 8;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    u32x4 z = {0u, 0u, 0u, 0u};
-                    reg[i][j] = (kb + j < k_end) ? *reinterpret_cast<const u32x4*>(ptr[i] + (size_t)(k0 + j) * ld) : z;
-                }
-            }
-        }
-    }
-    __device__ inline void store(char* lds) const {
-#pragma unroll
-        for (int i = 0; i < N; ++i) {
-            const int u = threadIdx.x + 256 * i;
-            if (u < ROWS) {
-                const int kblock = u & 7, r0 = (u >> 3) * 8;
-#pragma unroll
-                for (int m = 0; m < 8; ++m) {
-                    const uint32_t sel = (m & 1) ? 0x07060302u : 0x05040100u;
-                    u32x4 o;
-                    o.x = __builtin_amdgcn_perm(reg[i][1][m >> 1], reg[i][0][m >> 1], sel);
-                    o.y = __builtin_amdgcn_perm(reg[i][3][m >> 1], reg[i][2][m >> 1], sel);
-                    o.z = __builtin_amdgcn_perm(reg[i][5][m >> 1], reg[i][4][m >> 1], sel);
-                    o.w = __builtin_amdgcn_perm(reg[i][7][m >> 1], reg[i][6][m >> 1], sel);
-                    *reinterpret_cast<u32x4*>(lds + lds_off(r0 + m, kblock)) = o;
-                }
-            }
-        }
+    template <int M, int SET>
+    __device__ inline void store_one(char* lds) const {
+        const int u = threadIdx.x % ROWS;
+        const int kblock = u & 7, r0 = (u >> 3) * 8;
+        constexpr uint32_t sel = (M & 1) ? 0x07060302u : 0x05040100u;
+        u32x4 o;
+#ifdef FINE_DBG_NOPERM
+        o = reg[SET][M];
+        *reinterpret_cast<u32x4*>(lds + lds_off(r0 + M, kblock)) = o;
+        return;
+#endif
+        o.x = __builtin_amdgcn_perm(reg[SET][1][M >> 1], reg[SET][0][M >> 1], sel);
+        o.y = __builtin_amdgcn_perm(reg[SET][3][M >> 1], reg[SET][2][M >> 1], sel);
+        o.z = __builtin_amdgcn_perm(reg[SET][5][M >> 1], reg[SET][4][M >> 1], sel);
+        o.w = __builtin_amdgcn_perm(reg[SET][7][M >> 1], reg[SET][6][M >> 1], sel);
+        *reinterpret_cast<u32x4*>(lds + lds_off(r0 + M, kblock)) = o;
     }
 };
 
-// One 64-wide k-step of MFMAs out of LDS.
-template <int WAVES_M, int WAVES_N, int WM, int WN>
-__device__ inline void mma_step(const char* sA, const char* sB, f32x16 (&acc)[WM][WN]) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int r = lane & 31, half = lane >> 5;
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-        bf16x8 af[WM], bfr[WN];
-#pragma unroll
-        for (int mi = 0; mi < WM; ++mi)
-            af[mi] = *reinterpret_cast<const bf16x8*>(sA + lds_off((wm * WM + mi) * 32 + r, 2 * kk + half));
-#pragma unroll
-        for (int ni = 0; ni < WN; ++ni)
-            bfr[ni] = *reinterpret_cast<const bf16x8*>(sB + lds_off((wn * WN + ni) * 32 + r, 2 * kk + half));
-#pragma unroll
-        for (int mi = 0; mi < WM; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < WN; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-    }
+// Accumulator layout.  The MFMAs are issued with the operands swapped (weights fragment first),
+// so each 32x32 accumulator tile holds the TRANSPOSED output tile: lane l owns output row
+// (l & 31) of the tile and, in registers 4*rg .. 4*rg+3, the four consecutive output columns
+// 8*rg + 4*(l >> 5) + {0,1,2,3}.  Four neighbouring columns per lane make 8-byte (bf16) or
+// 16-byte (fp32) stores possible.
+__device__ inline int acc_m() { return threadIdx.x & 31; }
+__device__ inline int acc_n(int rg) { return 8 * rg + 4 * ((threadIdx.x & 63) >> 5); }
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
 }
 
-// The double-buffered k-loop shared by every grouped GEMM.  load(kt) brings k-tile kt from
-// global memory into the loaders' registers, store(sA, sB) writes those registers into one
-// LDS buffer pair.  On return every wave has finished reading LDS.
-template <int WAVES_M, int WAVES_N, int WM, int WN, typename Load, typename Store>
-__device__ inline void k_loop(int nk, char* smem, f32x16 (&acc)[WM][WN], Load load, Store store) {
-    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
-    auto sA = [&](int buf) { return smem + buf * (BM * 128); };
-    auto sB = [&](int buf) { return smem + 2 * BM * 128 + buf * (BN * 128); };
-    if (nk <= 0) return;
-    load(0);
-    store(sA(0), sB(0));
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) load(kt + 1);
-        mma_step<WAVES_M, WAVES_N, WM, WN>(sA(cur), sB(cur), acc);
-        if (kt + 1 < nk) store(sA(cur ^ 1), sB(cur ^ 1));
+// Moves a tile of bf16 values from the accumulator layout to a row-contiguous one through LDS,
+// so that global stores are 8 bytes per lane and contiguous along rows.  The tile has
+// WAVES_M*WM*32 rows and BNC = WAVES_N*NT*32 columns; wave (wm, wn) supplies val(mi, t, rg, q) for row
+// (wm*WM+mi)*32 + (l&31) and column (wn*NT+t)*32 + acc_n(rg) + q.  It is staged WMC row-tiles
+// per wave at a time (LDS: WAVES_M*WMC*32 rows of BNC*2+8 bytes; the 8 bytes of padding spread
+// the 8-byte LDS writes of 32 lanes over all banks); emit(row, col, four bf16) is then called
+// once for every group of four columns.  Every wave must have finished reading the operand
+// tiles in `smem` before the call; on return `smem` may be reused.
+template <int WAVES_M, int WAVES_N, int WM, int NT, int WMC, typename Val, typename Emit>
+__device__ inline void stage_tile_bf16(char* smem, Val val, Emit emit) {
+    constexpr int BNC = WAVES_N * NT * 32;
+    constexpr int PITCH = BNC * 2 + 8;
+    constexpr int ROWS_PASS = WAVES_M * WMC * 32;
+    constexpr int UNITS = ROWS_PASS * (BNC / 4);          // 8-byte units per pass
+    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
+    static_for<WM / WMC>([&](auto pass) {
+        static_for<WMC>([&](auto ml) {
+            constexpr int mi = pass.value * WMC + ml.value;
+            const int crow = (wm * WMC + ml.value) * 32 + acc_m();
+            static_for<NT>([&](auto t) {
+                static_for<4>([&](auto rg) {
+                    const int col = (wn * NT + t.value) * 32 + acc_n(rg.value);
+                    uint2 v;
+                    v.x = pack_bf16x2(val(IntC<mi>{}, t, rg, IntC<0>{}), val(IntC<mi>{}, t, rg, IntC<1>{}));
+                    v.y = pack_bf16x2(val(IntC<mi>{}, t, rg, IntC<2>{}), val(IntC<mi>{}, t, rg, IntC<3>{}));
+                    *reinterpret_cast<uint2*>(smem + crow * PITCH + col * 2) = v;
+                });
+            });
+        });
         __syncthreads();
-    }
+        for (int u = threadIdx.x; u < UNITS; u += kThreads) {
+            const int crow = u / (BNC / 4), cu = u % (BNC / 4);
+            const int row = ((crow / (WMC * 32)) * WM + pass.value * WMC) * 32 + crow % (WMC * 32);
+            emit(row, cu * 4, *reinterpret_cast<const uint2*>(smem + crow * PITCH + cu * 8));
+        }
+        __syncthreads();
+    });
 }
 
-// Blocks are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the
-// work list so that blocks sharing an L2 also share operand tiles.
-__device__ inline int xcd_contiguous_id() {
-    const int b = blockIdx.x, n = gridDim.x;
-    return (n % 8 == 0) ? (b % 8) * (n / 8) + b / 8 : b;
+// The plain case: the staged values go to C[row0 + row][col0 + col].
+template <int WAVES_M, int WAVES_N, int WM, int NT, int WMC, typename Val>
+__device__ inline void store_tile_bf16(char* smem, Val val, uint16_t* __restrict__ C, size_t ldc, int row0,
+                                       int rows_valid, int col0, int cols_valid) {
+    stage_tile_bf16<WAVES_M, WAVES_N, WM, NT, WMC>(smem, val, [&](int row, int col, uint2 v) {
+        if (row < rows_valid && col0 + col < cols_valid)
+            *reinterpret_cast<uint2*>(C + (size_t)(row0 + row) * ldc + col0 + col) = v;
+    });
 }
-
-// Row and column (inside the 32x32 MFMA tile) of accumulator register r of this lane.
-__device__ inline int acc_row(int r) { return 8 * (r >> 2) + 4 * ((threadIdx.x & 63) >> 5) + (r & 3); }
-__device__ inline int acc_col() { return threadIdx.x & 31; }
 
 template <int WM, int WN>
 __device__ inline void zero_acc(f32x16 (&acc)[WM][WN]) {
@@ -194,6 +210,188 @@ __device__ inline void zero_acc(f32x16 (&acc)[WM][WN]) {
         for (int ni = 0; ni < WN; ++ni)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+}
+
+// Blocks are dealt to the 8 XCDs round-robin; give each XCD a contiguous range of the
+// work list so that blocks sharing an L2 also share operand tiles.
+__device__ inline int xcd_contiguous_id() {
+    const int b = blockIdx.x, n = gridDim.x;
+    return (n % 8 == 0) ? (b % 8) * (n / 8) + b / 8 : b;
+}
+
+constexpr int share_begin(int slot, int total, int slots) { return (total * slot) / slots; }
+
+#ifdef FINE_PROFILE_LOOP
+// scratch instrumentation (never in the shipped build): cycle stamps of block 0, wave 0
+static __device__ unsigned long long g_prof[128 * 8];
+#define FINE_PROF(slot)                                                                          \
+    do {                                                                                         \
+        if (blockIdx.x == 0 && threadIdx.x == 0 && kt < 64) g_prof[kt * 8 + (slot)] = clock64(); \
+    } while (0)
+#else
+#define FINE_PROF(slot) do { } while (0)
+#endif
+
+// ---------------------------------------------------------------------------
+// One k-step (64 k-values) with a hand-fixed instruction order.
+//
+// Measured on MI355X: under load a global load takes a couple of thousand cycles to return
+// (longer than the MFMAs of one step), and the load path accepts 64 bytes per clock per CU,
+// i.e. a step's operand tiles need on the order of a thousand issue cycles.  A schedule that
+// issues a tile's loads in one half of a step and writes them to LDS in the other half is
+// bound by that latency, not by the MFMAs.  So the memory pipeline is kept busy all the time
+// and every load is given D full steps (D = 1 or 2) before its data is needed:
+//   step kt computes on LDS buffer kt&1, writes k-tile kt+1 from register set SET to the other
+//   buffer and reloads SET with k-tile kt+1+D.  With D = 2 the two register sets alternate
+//   (SET = (kt+1)&1); with D = 1 LoaderKC keeps one set and reloads each piece right after
+//   writing it, while LoaderMC, whose writes need all eight loads of a set, drains one set
+//   and fills the other.
+// The step is cut into slots of two MFMAs; each slot carries its share of the fragment reads
+// of sub-step kk+1 and of the LDS writes / global loads, and a scheduling barrier pins the
+// slots.  STORE / LOAD switch the two halves off for the last steps.
+// ---------------------------------------------------------------------------
+template <int WAVES_M, int WAVES_N, int WM, int WN, int D, int PAR, bool STORE, bool LOAD, typename LA, typename LB>
+__device__ inline void k_step(const char* sA, const char* sB, char* nA, char* nB, f32x16 (&acc)[WM][WN],
+                              LA& la, LB& lb, const KTile next) {
+    constexpr int MF = WM * WN;                 // MFMAs per sub-step
+    constexpr int SL = MF / 2;                  // slots per sub-step
+    constexpr int S = 4 * SL;                   // slots per step
+    constexpr int DSR = WM + WN;                // fragment reads per sub-step
+    constexpr int NA = LA::kLoads, NB = LB::kLoads;
+    static_assert(LA::kLoads == LA::kStores && LB::kLoads == LB::kStores, "one write per load");
+    // register sets: which one is written to LDS now, which one is (re)loaded now
+    constexpr int ST_A = (D == 2) ? PAR : (LA::kPieceRecycle ? 0 : PAR);
+    constexpr int LD_A = (D == 2) ? PAR : (LA::kPieceRecycle ? 0 : (PAR ^ 1));
+    constexpr int ST_B = (D == 2) ? PAR : (LB::kPieceRecycle ? 0 : PAR);
+    constexpr int LD_B = (D == 2) ? PAR : (LB::kPieceRecycle ? 0 : (PAR ^ 1));
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int r = lane & 31, half = lane >> 5;
+    bf16x8 af[2][WM], bfr[2][WN];
+
+    auto read_frag = [&](auto kk, auto idx, auto set) {      // idx < WM: A fragment, else B fragment
+#ifdef FINE_DBG_NOLDSREAD
+        if (kk.value > 0) return;
+#endif
+        if constexpr (idx.value < WM)
+            af[set.value][idx.value] = *reinterpret_cast<const bf16x8*>(
+                sA + lds_off((wm * WM + idx.value) * 32 + r, 2 * kk.value + half));
+        else
+            bfr[set.value][idx.value - WM] = *reinterpret_cast<const bf16x8*>(
+                sB + lds_off((wn * WN + (idx.value - WM)) * 32 + r, 2 * kk.value + half));
+    };
+    // Side work, in issue order: the writes of B (its data is the oldest), the writes and
+    // reloads of A (piece by piece where a piece may be reloaded at once), the loads of B.
+    auto side_op = [&](auto op) {
+        constexpr int o = op.value;
+#ifdef FINE_DBG_NOSTORE
+        if constexpr (o < NB || (o < NB + 2 * NA && (LA::kPieceRecycle ? ((o - NB) % 2 == 0) : (o - NB < NA)))) return;
+#endif
+        if constexpr (o < NB) {
+            if constexpr (STORE) lb.template store_one<o, ST_B>(nB);
+        } else if constexpr (o < NB + 2 * NA) {
+            constexpr int q = o - NB;
+            constexpr bool is_store = LA::kPieceRecycle ? (q % 2 == 0) : (q < NA);
+            constexpr int p = LA::kPieceRecycle ? q / 2 : (q < NA ? q : q - NA);
+            if constexpr (is_store) {
+                if constexpr (STORE) la.template store_one<p, ST_A>(nA);
+            } else {
+#ifndef FINE_DBG_NOLOADA
+                if constexpr (LOAD) la.template load_one<p, LD_A>(next.a, next.end);
+#endif
+            }
+        } else {
+#ifndef FINE_DBG_NOLOADB
+            if constexpr (LOAD) lb.template load_one<o - NB - 2 * NA, LD_B>(next.b, next.end);
+#endif
+        }
+    };
+    constexpr int NOPS = 2 * (NA + NB);
+
+    static_for<DSR>([&](auto i) { read_frag(IntC<0>{}, i, IntC<0>{}); });
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<4>([&](auto kk) {
+        static_for<SL>([&](auto j) {
+            constexpr int slot = kk.value * SL + j.value;
+            constexpr int cur = kk.value & 1;
+            static_for<2>([&](auto t) {
+                constexpr int m = 2 * j.value + t.value;
+                constexpr int mi = m / WN, ni = m % WN;
+#ifdef FINE_DBG_NOMFMA
+                if (af[cur][mi][0] == (__bf16)12345.f && bfr[cur][ni][1] == (__bf16)777.f) acc[mi][ni][0] += 1.f;
+#else
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
+#endif
+            });
+            if constexpr (kk.value < 3) {      // fragment reads of the next sub-step
+                constexpr int b = share_begin(j.value, DSR, SL), e = share_begin(j.value + 1, DSR, SL);
+                static_for<e - b>([&](auto q) { read_frag(IntC<kk.value + 1>{}, IntC<b + q.value>{}, IntC<cur ^ 1>{}); });
+            }
+            {
+                constexpr int b = share_begin(slot, NOPS, S), e = share_begin(slot + 1, NOPS, S);
+                static_for<e - b>([&](auto q) { side_op(IntC<b + q.value>{}); });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    });
+}
+
+// The k-loop shared by every grouped GEMM: tile(kt) says where k-tile kt is; it is called
+// exactly once for each kt = 0 .. nk-1, in order.  D = how many steps ahead of its LDS write
+// a tile is loaded (see k_step).  On return every wave has finished reading LDS.
+template <int WAVES_M, int WAVES_N, int WM, int WN, int D, typename LA, typename LB, typename Tile>
+__device__ inline void k_loop(int nk, char* smem, f32x16 (&acc)[WM][WN], LA& la, LB& lb, Tile tile) {
+    constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    auto sA = [&](int buf) { return smem + buf * (BM * 128); };
+    auto sB = [&](int buf) { return smem + 2 * BM * 128 + buf * (BN * 128); };
+    if (nk <= 0) return;
+    KTile last{0, 0, 0};
+    int fetched = 0;                                     // tiles asked for so far
+    auto next_tile = [&]() {                             // past the end: the last tile again (never used)
+        if (fetched < nk) { last = tile(fetched); }
+        ++fetched;
+        return last;
+    };
+    {   // k-tile 0 goes to LDS buffer 0 at once; the next D tiles wait in the registers
+        const KTile t0 = next_tile();
+        static_for<LA::kLoads>([&](auto i) { la.template load_one<i.value, 0>(t0.a, t0.end); });
+        static_for<LB::kLoads>([&](auto i) { lb.template load_one<i.value, 0>(t0.b, t0.end); });
+        static_for<LA::kStores>([&](auto i) { la.template store_one<i.value, 0>(sA(0)); });
+        static_for<LB::kStores>([&](auto i) { lb.template store_one<i.value, 0>(sB(0)); });
+        // tile 1: step 0 writes it from set ST(PAR = 0); D == 2 uses SET = (kt+1)&1 = 1 there
+        const KTile t1 = next_tile();
+        if constexpr (D == 2) {
+            static_for<LA::kLoads>([&](auto i) { la.template load_one<i.value, 1>(t1.a, t1.end); });
+            static_for<LB::kLoads>([&](auto i) { lb.template load_one<i.value, 1>(t1.b, t1.end); });
+            const KTile t2 = next_tile();
+            static_for<LA::kLoads>([&](auto i) { la.template load_one<i.value, 0>(t2.a, t2.end); });
+            static_for<LB::kLoads>([&](auto i) { lb.template load_one<i.value, 0>(t2.b, t2.end); });
+        } else {
+            static_for<LA::kLoads>([&](auto i) { la.template load_one<i.value, 0>(t1.a, t1.end); });
+            static_for<LB::kLoads>([&](auto i) { lb.template load_one<i.value, 0>(t1.b, t1.end); });
+        }
+    }
+    __syncthreads();
+    // PAR of step kt: D == 2: set (kt+1)&1;  D == 1: LoaderMC drains set kt&1.
+    constexpr int P0 = (D == 2) ? 1 : 0;
+    int kt = 0;
+    for (; kt + 2 < nk; kt += 2) {       // both steps write a tile that will be used
+        FINE_PROF(0);
+        k_step<WAVES_M, WAVES_N, WM, WN, D, P0, true, true>(sA(0), sB(0), sA(1), sB(1), acc, la, lb, next_tile());
+        FINE_PROF(3);
+        __syncthreads();
+        FINE_PROF(4);
+        k_step<WAVES_M, WAVES_N, WM, WN, D, P0 ^ 1, true, true>(sA(1), sB(1), sA(0), sB(0), acc, la, lb, next_tile());
+        __syncthreads();
+    }
+    if (nk - kt == 2) {                  // kt even: buffers 0 then 1
+        k_step<WAVES_M, WAVES_N, WM, WN, D, P0, true, false>(sA(0), sB(0), sA(1), sB(1), acc, la, lb, last);
+        __syncthreads();
+        k_step<WAVES_M, WAVES_N, WM, WN, D, P0 ^ 1, false, false>(sA(1), sB(1), nullptr, nullptr, acc, la, lb, last);
+    } else {
+        k_step<WAVES_M, WAVES_N, WM, WN, D, P0, false, false>(sA(0), sB(0), nullptr, nullptr, acc, la, lb, last);
+    }
+    __syncthreads();
 }
 
 }  // namespace mfma
