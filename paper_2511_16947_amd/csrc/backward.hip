@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void k_bwd_dh(const uint16_t* __restrict__ dy,
                         const float dh = bf16_bits_to_float((uint16_t)(dhw[w] >> (16 * hlf)));
                         const float a = bf16_bits_to_float((uint16_t)(aw[w] >> (16 * hlf)));
                         const float b = bf16_bits_to_float((uint16_t)(bw[w] >> (16 * hlf)));
-                        const float sg = 1.f / (1.f + __expf(-a));
+                        const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-a));
                         o_da[hlf] = dh * b * sg * (1.f + a * (1.f - sg));
                         o_db[hlf] = dh * a * sg;
                         o_h[hlf] = a * sg * b;

@@ -5,7 +5,9 @@
 //   GEMM 2: Y = H Wd.
 // Both run as persistent kernels over a device-built work list (row tile x column
 // tile), so that nothing about segment lengths has to reach the host.
-#include "gemm_mfma.h"
+#include <cmath>
+
+#include "gemm_w8.h"
 
 namespace fine {
 
@@ -13,27 +15,27 @@ namespace {
 
 using namespace mfma;
 
-__device__ inline float silu_mul(float a, float b) { return a / (1.f + __expf(-a)) * b; }
+// silu(a) * b with the hardware reciprocal (1 ulp), far inside the bf16 rounding of the result
+__device__ inline float silu_mul(float a, float b) { return a * b * __builtin_amdgcn_rcpf(1.f + __expf(-a)); }
 
 // EPI 0: GEMM 1 (A = x_perm, B0/B1 = Wg/Wu [E,Kd,N]; C = H [P,N]; act [P,2N] optional)
 // EPI 1: GEMM 2 (A = H, B0 = Wd [E,Kd,N]; C = y_perm [P,N])
+// 4 waves: every thread loads its share of both operand tiles; 8 waves: unified filler.
 template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
-__global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A, int lda,
-                                                  const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
-                                                  size_t b_expert_stride, int Kd, int N,
-                                                  uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ act,
-                                                  const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+__device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, int lda, const uint16_t* __restrict__ B0,
+                                              const uint16_t* __restrict__ B1, size_t b_expert_stride, int Kd, int N,
+                                              uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ act,
+                                              const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     constexpr int BNC = (EPI == 0) ? BN / 2 : BN;      // output columns per block
-    static_assert(WAVES_M * WAVES_N == 4, "4 waves");
+    constexpr bool W8 = WAVES_M * WAVES_N == 8;
+    static_assert(WAVES_M * WAVES_N == 4 || (W8 && WAVES_N == 4 && WM == 4 && WN == 2), "4 waves, or 2 x 4 waves on 256 x 256");
     static_assert(EPI != 0 || WN % 2 == 0, "gate/up pairs");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int ntn = (N + BNC - 1) / BNC;
     const int ntm = *count;
     const int total = ntm * ntn;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int nk = Kd / BK;
 
     for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
@@ -48,10 +50,11 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
 #define FINE_PROF_TILE(slot) do { } while (0)
 #endif
         FINE_PROF_TILE(0);
-        LoaderKC<BM> la;
-        la.init([&](int r) { return A + (size_t)(te.row0 + min(r, te.rows - 1)) * lda; });
-        LoaderMC<BN, false> lb;
-        lb.init([&](int r8) {
+#ifdef FINE_PROFILE_LOOP
+        if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + 5] = wall_clock64();
+#endif
+        auto a_row = [&](int r) { return (size_t)(te.row0 + min(r, te.rows - 1)) * lda; };
+        auto b_col = [&](int r8) {
             const int nb = r8 * 8;
             if (EPI == 0) {
                 const int q = nb >> 5, within = nb & 31;
@@ -60,19 +63,42 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
             } else {
                 return Bg + min(n0 + nb, N - 8);
             }
-        }, (size_t)N);
+        };
+        auto k_tile = [&](int kt) { return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)kt * BK, Kd}; };
 
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
 
-        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, [&](int kt) {
-            return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)kt * BK, Kd};
-        });
+        if constexpr (W8) {
+            const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+            RegOperand<WM> oa;
+            oa.init(A + (size_t)te.row0 * lda, [&](int r) { return (size_t)min(r, te.rows - 1) * lda; },
+                    (wave / WAVES_N) * WM * 32);
+            DmaOperand<WN> ob;
+            const int wn = wave % WAVES_N;
+            const uint32_t w_bytes = (uint32_t)((size_t)Kd * N * 2);
+            if constexpr (EPI == 0) {
+                // panel 0 = 128 gate columns, panel 1 = the matching up columns; a wave's two
+                // fragments are the same 32 columns of both
+                ob.init(Bg, Bu, w_bytes, [&](int, int c) { return min(n0 + 8 * c, N - 8); }, (size_t)N,
+                        [&](int f) { return 128 * f + 32 * wn; });
+            } else {
+                ob.init(Bg, Bg, w_bytes, [&](int p, int c) { return min(n0 + 128 * p + 8 * c, N - 8); }, (size_t)N,
+                        [&](int f) { return 64 * wn + 32 * f; });
+            }
+            k_loop8(nk, smem, acc, oa, ob, k_tile);
+        } else {
+            LoaderKC<BM> la;
+            la.init([&](int r) { return A + a_row(r); });
+            LoaderMC<BN, false> lb;
+            lb.init(b_col, (size_t)N);
+            k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, k_tile);
+        }
 
         // epilogue: LDS-staged, 8-byte coalesced stores
         FINE_PROF_TILE(1);
+        constexpr int WMC = (BM * (BNC * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
         if constexpr (EPI == 0) {
-            constexpr int WMC = (BM * (BNC * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
             if (act != nullptr) {
                 store_tile_bf16<WAVES_M, WAVES_N, WM, WN / 2, WMC>(
                     smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][2 * t.value][4 * rg.value + q.value]; },
@@ -89,13 +115,40 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
                 },
                 C, (size_t)ldc, te.row0, te.rows, n0, N);
         } else {
-            constexpr int WMC = (BM * (BNC * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
             store_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(
                 smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
                 C, (size_t)ldc, te.row0, te.rows, n0, N);
         }
         FINE_PROF_TILE(2);
+#ifdef FINE_PROFILE_LOOP
+        if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + 6] = wall_clock64();
+#endif
     }
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
+__global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A, int lda,
+                                                  const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
+                                                  size_t b_expert_stride, int Kd, int N,
+                                                  uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ act,
+                                                  const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+    ffn_gemm_body<WAVES_M, WAVES_N, WM, WN, EPI>(A, lda, B0, B1, b_expert_stride, Kd, N, C, ldc, act, tiles, count);
+}
+
+// 8 waves: two per SIMD, each with 128 architectural and 128 accumulator registers
+template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
+__global__ __launch_bounds__(512) void k_ffn_gemm_w8(const uint16_t* __restrict__ A, int lda,
+                                                     const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
+                                                     size_t b_expert_stride, int Kd, int N,
+                                                     uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ act,
+                                                     const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+    ffn_gemm_body<WAVES_M, WAVES_N, WM, WN, EPI>(A, lda, B0, B1, b_expert_stride, Kd, N, C, ldc, act, tiles, count);
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
+constexpr auto ffn_kernel() {
+    if constexpr (WAVES_M * WAVES_N == 8) return k_ffn_gemm_w8<WAVES_M, WAVES_N, WM, WN, EPI>;
+    else return k_ffn_gemm<WAVES_M, WAVES_N, WM, WN, EPI>;
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
@@ -106,8 +159,9 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     auto* h = reinterpret_cast<uint16_t*>(h_buf);
     FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
     const size_t lds = (size_t)2 * (BM + BN) * 128;
-    auto k1 = k_ffn_gemm<WAVES_M, WAVES_N, WM, WN, 0>;
-    auto k2 = k_ffn_gemm<WAVES_M, WAVES_N, WM, WN, 1>;
+    auto k1 = ffn_kernel<WAVES_M, WAVES_N, WM, WN, 0>();
+    auto k2 = ffn_kernel<WAVES_M, WAVES_N, WM, WN, 1>();
+    constexpr int threads = WAVES_M * WAVES_N * 64;
     static bool attr_done = false;      // per instantiation
     if (!attr_done) {
         FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k1, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
@@ -117,12 +171,12 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     const int blocks_per_cu = (lds <= 80 * 1024) ? 2 : 1;
     const int grid = 256 * blocks_per_cu;
     if (gemm1) {
-        hipLaunchKernelGGL(k1, dim3(grid), dim3(256), lds, st, (const uint16_t*)x_perm, s.d, (const uint16_t*)wg,
+        hipLaunchKernelGGL(k1, dim3(grid), dim3(threads), lds, st, (const uint16_t*)x_perm, s.d, (const uint16_t*)wg,
                            (const uint16_t*)wu, (size_t)s.d * s.f, s.d, s.f, h, s.f, (uint16_t*)act_save, tiles, count);
         FINE_LAUNCH_CHECK();
     }
     if (gemm2) {
-        hipLaunchKernelGGL(k2, dim3(grid), dim3(256), lds, st, (const uint16_t*)h, s.f, (const uint16_t*)wd,
+        hipLaunchKernelGGL(k2, dim3(grid), dim3(threads), lds, st, (const uint16_t*)h, s.f, (const uint16_t*)wd,
                            (const uint16_t*)nullptr, (size_t)s.f * s.d, s.f, s.d, (uint16_t*)y_perm, s.d,
                            (uint16_t*)nullptr, tiles, count);
         FINE_LAUNCH_CHECK();
@@ -130,14 +184,27 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     return FINE_OK;
 }
 
-int pick_tile(const fine_shape& s) {
+// Tile choice for one of the two GEMMs (n_out output columns).
+//   3: 256 x 256 on 8 waves - the fastest per tile, but a launch should fill the 256 CUs about
+//      twice, and segments should be long enough not to waste most of a 256-row tile;
+//   2: 128 x 256, 1: 64 x 256 on 4 waves for short segments.
+int pick_tile(const fine_shape& s, int n_ranks, int n_out, int bnc3) {
+    int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
+    if (tile != 0) return tile;
     // expected rows of a (rank, expert) segment when every expert is on every rank: a
     // rank's ceil(P/G) rows span about E/G + 1 experts
     const double P = (double)s.T * s.K;
     const double seg_rows = (P / s.G) / ((double)s.E / s.G + 1.0);
-    int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
-    if (tile == 0) tile = seg_rows >= 384.0 ? 3 : (seg_rows >= 96.0 ? 2 : 1);
-    return tile;
+    const double tiles3 = std::ceil(P * n_ranks / s.G / 256.0) * std::ceil((double)n_out / bnc3);
+    if (seg_rows >= 384.0 && tiles3 >= 448.0) return 3;
+    return seg_rows >= 96.0 ? 2 : 1;
+}
+
+template <typename... Args>
+int run_ffn_tile(int tile, Args... args) {
+    if (tile == 3) return run_ffn<2, 4, 4, 2>(args...);
+    if (tile == 2) return run_ffn<2, 2, 2, 4>(args...);
+    return run_ffn<1, 4, 2, 2>(args...);
 }
 
 }  // namespace
@@ -146,15 +213,15 @@ int launch_ffn_parts(const fine_shape& s, int rank_lo, int rank_hi, const void* 
                      const void* wu, const void* wd, const int32_t* seg_off, void* h_buf, void* y_perm,
                      void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, bool gemm1, bool gemm2,
                      hipStream_t st) {
-    const int tile = pick_tile(s);
-    if (tile == 3)
-        return run_ffn<2, 2, 4, 4>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles,
-                                   count, max_tiles, gemm1, gemm2, st);
-    if (tile == 2)
-        return run_ffn<2, 2, 2, 4>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles,
-                                   count, max_tiles, gemm1, gemm2, st);
-    return run_ffn<1, 4, 2, 2>(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles, count,
-                               max_tiles, gemm1, gemm2, st);
+    const int t1 = pick_tile(s, rank_hi - rank_lo, s.f, 128), t2 = pick_tile(s, rank_hi - rank_lo, s.d, 256);
+    if (t1 == t2 || !gemm1 || !gemm2)
+        return run_ffn_tile(gemm1 ? t1 : t2, s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save,
+                            tiles, count, max_tiles, gemm1, gemm2, st);
+    // different row tiles: the work list is rebuilt between the two GEMMs (same stream)
+    FINE_TRY(run_ffn_tile(t1, s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles, count,
+                          max_tiles, true, false, st));
+    return run_ffn_tile(t2, s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles, count,
+                        max_tiles, false, true, st);
 }
 
 int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm,

@@ -149,8 +149,12 @@ struct LoaderMC {
 __device__ inline int acc_m() { return threadIdx.x & 31; }
 __device__ inline int acc_n(int rg) { return 8 * rg + 4 * ((threadIdx.x & 63) >> 5); }
 
+// two floats -> two bf16 (round to nearest even) in one v_cvt_pk_bf16_f32
 __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
-    return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Moves a tile of bf16 values from the accumulator layout to a row-contiguous one through LDS,
@@ -183,7 +187,7 @@ __device__ inline void stage_tile_bf16(char* smem, Val val, Emit emit) {
             });
         });
         __syncthreads();
-        for (int u = threadIdx.x; u < UNITS; u += kThreads) {
+        for (int u = threadIdx.x; u < UNITS; u += WAVES_M * WAVES_N * 64) {
             const int crow = u / (BNC / 4), cu = u % (BNC / 4);
             const int row = ((crow / (WMC * 32)) * WM + pass.value * WMC) * 32 + crow % (WMC * 32);
             emit(row, cu * 4, *reinterpret_cast<const uint2*>(smem + crow * PITCH + cu * 8));
