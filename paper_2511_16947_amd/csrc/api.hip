@@ -42,7 +42,8 @@ BwdWs bwd_ws_layout(const fine_shape& s) {
     w.h = o;     o = align_up(o + P * s.f * es, 256);
     w.dxp = o;   o = align_up(o + P * s.d * es, 256);
     w.tiles = o; o = align_up(o + (size_t)w.max_tiles * sizeof(TileEntry), 256);
-    w.count = o; o = align_up(o + 256, 256);
+    w.count = o; o = align_up(o + kCountBytes, 256);
+    w.sk = o;    o = align_up(o + kSkBytes, 256);
     w.total = o;
     return w;
 }

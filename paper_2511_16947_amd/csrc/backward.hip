@@ -243,7 +243,7 @@ int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, 
     if (act == nullptr) {      // recompute the pre-activations A | B
         auto* act_ws = reinterpret_cast<uint16_t*>(ws + L.act);
         FINE_TRY(launch_ffn_parts(s, 0, s.G, x_perm, wg, wu, wd, seg_off, h, nullptr, act_ws, tiles, count, L.max_tiles,
-                                  true, false, st));
+                                  reinterpret_cast<float*>(ws + L.sk), true, false, st));
         act = act_ws;
     }
     const double P = (double)s.T * s.K;

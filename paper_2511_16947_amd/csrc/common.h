@@ -84,10 +84,18 @@ struct TileEntry {
     int32_t seg_rows;  // rows of the whole segment
 };
 
+// The count block: int32 number of row tiles, and from int32 index kSkCounterOffset on 256
+// arrival counters for tiles cut along k (zero between launches).  Partial sums of such tiles:
+// two slots of one 256 x 256 fp32 tile for each of the 256 blocks of a launch.
+constexpr size_t kCountBytes = 2048;
+constexpr int kSkCounterOffset = 64;
+constexpr size_t kSkBytes = (size_t)512 * 256 * 256 * 4;
+
 struct FfnWs {
     size_t h;          // dtype [P][f]
-    size_t tiles;      // TileEntry [max_tiles] followed by int32 count
-    size_t count;
+    size_t tiles;      // TileEntry [max_tiles]
+    size_t count;      // the count block
+    size_t sk;         // float partial sums (bf16 layers only)
     size_t total;
     int max_tiles;
 };
@@ -100,7 +108,8 @@ struct BwdWs {
     size_t h;          // dtype [P][f]
     size_t dxp;        // dtype [P][d]
     size_t tiles;
-    size_t count;
+    size_t count;      // the count block
+    size_t sk;         // float partial sums of tiles cut along k
     size_t total;
     int max_tiles;
 };
@@ -138,7 +147,7 @@ int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x
 
 int launch_ffn_parts(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, const void* wg,
                      const void* wu, const void* wd, const int32_t* seg_off, void* h_buf, void* y_perm,
-                     void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, bool gemm1, bool gemm2,
+                     void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, float* sk_partials, bool gemm1, bool gemm2,
                      hipStream_t st);
 
 int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, const void* y_perm,

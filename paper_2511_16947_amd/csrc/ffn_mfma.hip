@@ -20,12 +20,15 @@ __device__ inline float silu_mul(float a, float b) { return a * b * __builtin_am
 
 // EPI 0: GEMM 1 (A = x_perm, B0/B1 = Wg/Wu [E,Kd,N]; C = H [P,N]; act [P,2N] optional)
 // EPI 1: GEMM 2 (A = H, B0 = Wd [E,Kd,N]; C = y_perm [P,N])
-// 4 waves: every thread loads its share of both operand tiles; 8 waves: unified filler.
+// 4 waves: every thread loads its share of both operand tiles, whole tiles only.
+// 8 waves: see gemm_w8.h; the tiles that do not fill a whole round of the grid are cut along
+// k so that every block gets the same number of k-steps (sk_partials, sk_counters below).
 template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
 __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, int lda, const uint16_t* __restrict__ B0,
                                               const uint16_t* __restrict__ B1, size_t b_expert_stride, int Kd, int N,
                                               uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ act,
-                                              const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+                                              const TileEntry* __restrict__ tiles, int32_t* __restrict__ count,
+                                              float* __restrict__ sk_partials) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     constexpr int BNC = (EPI == 0) ? BN / 2 : BN;      // output columns per block
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
@@ -37,43 +40,20 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     const int ntm = *count;
     const int total = ntm * ntn;
     const int nk = Kd / BK;
+    f32x16 acc[WM][WN];
 
-    for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
+    // acc += (rows of tile `work`) x (its weight columns) over k-tiles [kb, kb + kn)
+    auto run_tile = [&](int work, int kb, int kn) {
         const TileEntry te = tiles[work % ntm];
         const int n0 = (work / ntm) * BNC;
         const uint16_t* Bg = B0 + (size_t)te.expert * b_expert_stride;
         const uint16_t* Bu = (EPI == 0) ? B1 + (size_t)te.expert * b_expert_stride : nullptr;
-
-#ifdef FINE_PROFILE_LOOP
-#define FINE_PROF_TILE(slot) do { if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + (slot)] = clock64(); } while (0)
-#else
-#define FINE_PROF_TILE(slot) do { } while (0)
-#endif
-        FINE_PROF_TILE(0);
-#ifdef FINE_PROFILE_LOOP
-        if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + 5] = wall_clock64();
-#endif
-        auto a_row = [&](int r) { return (size_t)(te.row0 + min(r, te.rows - 1)) * lda; };
-        auto b_col = [&](int r8) {
-            const int nb = r8 * 8;
-            if (EPI == 0) {
-                const int q = nb >> 5, within = nb & 31;
-                const int col = min(n0 + (q >> 1) * 32 + within, N - 8);
-                return ((q & 1) ? Bu : Bg) + col;
-            } else {
-                return Bg + min(n0 + nb, N - 8);
-            }
-        };
-        auto k_tile = [&](int kt) { return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)kt * BK, Kd}; };
-
-        f32x16 acc[WM][WN];
-        zero_acc<WM, WN>(acc);
-
+        auto a_row = [&](int r) { return (size_t)min(r, te.rows - 1) * lda; };
+        auto k_tile = [&](int kt) { return KTile{(ptrdiff_t)(kb + kt) * BK, (ptrdiff_t)(kb + kt) * BK, Kd}; };
         if constexpr (W8) {
             const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
             RegOperand<WM> oa;
-            oa.init(A + (size_t)te.row0 * lda, [&](int r) { return (size_t)min(r, te.rows - 1) * lda; },
-                    (wave / WAVES_N) * WM * 32);
+            oa.init(A + (size_t)te.row0 * lda, a_row, (wave / WAVES_N) * WM * 32);
             DmaOperand<WN> ob;
             const int wn = wave % WAVES_N;
             const uint32_t w_bytes = (uint32_t)((size_t)Kd * N * 2);
@@ -86,17 +66,28 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                 ob.init(Bg, Bg, w_bytes, [&](int p, int c) { return min(n0 + 128 * p + 8 * c, N - 8); }, (size_t)N,
                         [&](int f) { return 64 * wn + 32 * f; });
             }
-            k_loop8(nk, smem, acc, oa, ob, k_tile);
+            k_loop8(kn, smem, acc, oa, ob, k_tile);
         } else {
             LoaderKC<BM> la;
-            la.init([&](int r) { return A + a_row(r); });
+            la.init([&](int r) { return A + (size_t)te.row0 * lda + a_row(r); });
             LoaderMC<BN, false> lb;
-            lb.init(b_col, (size_t)N);
-            k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, k_tile);
+            lb.init([&](int r8) {
+                const int nb = r8 * 8;
+                if (EPI == 0) {
+                    const int q = nb >> 5, within = nb & 31;
+                    return ((q & 1) ? Bu : Bg) + min(n0 + (q >> 1) * 32 + within, N - 8);
+                } else {
+                    return Bg + min(n0 + nb, N - 8);
+                }
+            }, (size_t)N);
+            k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(kn, smem, acc, la, lb, k_tile);
         }
+    };
 
-        // epilogue: LDS-staged, 8-byte coalesced stores
-        FINE_PROF_TILE(1);
+    // LDS-staged epilogue of tile `work`, 8-byte coalesced stores
+    auto epilogue = [&](int work) {
+        const TileEntry te = tiles[work % ntm];
+        const int n0 = (work / ntm) * BNC;
         constexpr int WMC = (BM * (BNC * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
         if constexpr (EPI == 0) {
             if (act != nullptr) {
@@ -119,10 +110,104 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                 smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
                 C, (size_t)ldc, te.row0, te.rows, n0, N);
         }
-        FINE_PROF_TILE(2);
+    };
+
 #ifdef FINE_PROFILE_LOOP
-        if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + 6] = wall_clock64();
+#define FINE_PROF_TILE(slot) do { if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + (slot)] = (slot) >= 5 ? wall_clock64() : clock64(); } while (0)
+#else
+#define FINE_PROF_TILE(slot) do { } while (0)
 #endif
+    // Whole tiles first: as many full rounds of the grid as there are (4 waves: all tiles).
+    // 8 waves: the remaining rest < nblk tiles are rest * nk k-steps; block b takes steps
+    // [b * per, (b+1) * per) of that sequence.  A block that computes only part of a tile's k
+    // range writes its accumulators to its slot (two per block: a range begins and ends inside
+    // at most one tile each) and counts itself in; whoever counts in last adds the parts up in
+    // block order - the same sum whoever it is - and runs the epilogue.  Nobody waits.
+    __shared__ int s_last;
+    const int nblk = gridDim.x, bid = xcd_contiguous_id();
+    const int full = W8 ? (total / nblk) * nblk : total;
+    const int rest = total - full;
+    const int per = (rest * nk + nblk - 1) / nblk;
+    int32_t* counters = count + kSkCounterOffset;
+    auto slot_of = [&](int blk, int t) { return blk * 2 + (((blk * per) / nk) == t ? 0 : 1); };
+    // Partial sums travel as 8-byte agent-scope atomic stores and loads: they are written
+    // through and read past the per-XCD L2 one by one, so no cache-wide write-back or
+    // invalidate (a fence) is needed, which would cost every block on the XCD its cached
+    // operand tiles.
+    auto slot_ptr = [&](int slot, int j) {
+        return reinterpret_cast<uint64_t*>(sk_partials) + ((size_t)slot * 64 + j) * (WAVES_M * WAVES_N * 64) + threadIdx.x;
+    };
+    int next_whole = bid, u = bid * per;
+    const int u1 = min(rest * nk, u + per);
+    for (;;) {
+        int work, kb = 0, kn = nk;
+        if (next_whole < full) {
+            work = next_whole;
+            next_whole += nblk;
+        } else if (W8 && u < u1) {
+            const int t = u / nk;
+            kb = u - t * nk;
+            kn = min(nk - kb, u1 - u);
+            work = full + t;
+            u += kn;
+        } else {
+            break;
+        }
+        FINE_PROF_TILE(0);
+        FINE_PROF_TILE(5);
+        zero_acc<WM, WN>(acc);
+        run_tile(work, kb, kn);
+        FINE_PROF_TILE(1);
+        bool finish = true;
+        if constexpr (W8) {
+            if (kn != nk) {
+                const int t = work - full;
+                const int first = (t * nk) / per, last = (t * nk + nk - 1) / per;
+                const int mine = slot_of(bid, t);
+                uint64_t* wp = slot_ptr(mine, 0);
+                static_for<WM * WN>([&](auto m) {
+                    static_for<8>([&](auto q) {
+                        const f32x16& v = acc[m.value / WN][m.value % WN];
+                        const float2 pr = make_float2(v[2 * q.value], v[2 * q.value + 1]);
+                        __hip_atomic_store(wp, __builtin_bit_cast(uint64_t, pr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        wp += WAVES_M * WAVES_N * 64;
+                    });
+                    __builtin_amdgcn_sched_barrier(0);      // one group's addresses at a time
+                });
+                __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0): this thread's partial sums have been written
+                __syncthreads();
+                if (threadIdx.x == 0)
+                    s_last = __hip_atomic_fetch_add(&counters[t], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                             last - first;
+                __syncthreads();
+                finish = s_last != 0;
+                if (finish) {
+                    zero_acc<WM, WN>(acc);
+                    for (int blk = first; blk <= last; ++blk) {
+                        const uint64_t* rp = slot_ptr(slot_of(blk, t), 0);
+                        static_for<WM * WN>([&](auto m) {
+                            uint64_t v[8];
+                            static_for<8>([&](auto q) {
+                                v[q.value] = __hip_atomic_load(rp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                rp += WAVES_M * WAVES_N * 64;
+                            });
+                            f32x16& a = acc[m.value / WN][m.value % WN];
+                            static_for<8>([&](auto q) {
+                                const float2 pr = __builtin_bit_cast(float2, v[q.value]);
+                                a[2 * q.value] += pr.x;
+                                a[2 * q.value + 1] += pr.y;
+                            });
+                            __builtin_amdgcn_sched_barrier(0);      // keeps the loads from piling up in registers
+                        });
+                    }
+                    if (threadIdx.x == 0) counters[t] = 0;      // ready for the next launch
+                }
+                __syncthreads();
+            }
+        }
+        if (finish) epilogue(work);
+        FINE_PROF_TILE(2);
+        FINE_PROF_TILE(6);
     }
 }
 
@@ -131,8 +216,10 @@ __global__ __launch_bounds__(256) void k_ffn_gemm(const uint16_t* __restrict__ A
                                                   const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
                                                   size_t b_expert_stride, int Kd, int N,
                                                   uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ act,
-                                                  const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
-    ffn_gemm_body<WAVES_M, WAVES_N, WM, WN, EPI>(A, lda, B0, B1, b_expert_stride, Kd, N, C, ldc, act, tiles, count);
+                                                  const TileEntry* __restrict__ tiles, int32_t* __restrict__ count,
+                                                  float* __restrict__ sk_partials) {
+    ffn_gemm_body<WAVES_M, WAVES_N, WM, WN, EPI>(A, lda, B0, B1, b_expert_stride, Kd, N, C, ldc, act, tiles, count,
+                                                 sk_partials);
 }
 
 // 8 waves: two per SIMD, each with 128 architectural and 128 accumulator registers
@@ -141,8 +228,10 @@ __global__ __launch_bounds__(512) void k_ffn_gemm_w8(const uint16_t* __restrict_
                                                      const uint16_t* __restrict__ B0, const uint16_t* __restrict__ B1,
                                                      size_t b_expert_stride, int Kd, int N,
                                                      uint16_t* __restrict__ C, int ldc, uint16_t* __restrict__ act,
-                                                     const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
-    ffn_gemm_body<WAVES_M, WAVES_N, WM, WN, EPI>(A, lda, B0, B1, b_expert_stride, Kd, N, C, ldc, act, tiles, count);
+                                                     const TileEntry* __restrict__ tiles, int32_t* __restrict__ count,
+                                                     float* __restrict__ sk_partials) {
+    ffn_gemm_body<WAVES_M, WAVES_N, WM, WN, EPI>(A, lda, B0, B1, b_expert_stride, Kd, N, C, ldc, act, tiles, count,
+                                                 sk_partials);
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
@@ -154,7 +243,7 @@ constexpr auto ffn_kernel() {
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, const void* wg, const void* wu,
             const void* wd, const int32_t* seg_off, void* h_buf, void* y_perm, void* act_save, TileEntry* tiles,
-            int32_t* count, int max_tiles, bool gemm1, bool gemm2, hipStream_t st) {
+            int32_t* count, int max_tiles, float* sk_partials, bool gemm1, bool gemm2, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     auto* h = reinterpret_cast<uint16_t*>(h_buf);
     FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
@@ -172,21 +261,22 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     const int grid = 256 * blocks_per_cu;
     if (gemm1) {
         hipLaunchKernelGGL(k1, dim3(grid), dim3(threads), lds, st, (const uint16_t*)x_perm, s.d, (const uint16_t*)wg,
-                           (const uint16_t*)wu, (size_t)s.d * s.f, s.d, s.f, h, s.f, (uint16_t*)act_save, tiles, count);
+                           (const uint16_t*)wu, (size_t)s.d * s.f, s.d, s.f, h, s.f, (uint16_t*)act_save, tiles, count, sk_partials);
         FINE_LAUNCH_CHECK();
     }
     if (gemm2) {
         hipLaunchKernelGGL(k2, dim3(grid), dim3(threads), lds, st, (const uint16_t*)h, s.f, (const uint16_t*)wd,
                            (const uint16_t*)nullptr, (size_t)s.f * s.d, s.f, s.d, (uint16_t*)y_perm, s.d,
-                           (uint16_t*)nullptr, tiles, count);
+                           (uint16_t*)nullptr, tiles, count, sk_partials);
         FINE_LAUNCH_CHECK();
     }
     return FINE_OK;
 }
 
 // Tile choice for one of the two GEMMs (n_out output columns).
-//   3: 256 x 256 on 8 waves - the fastest per tile, but a launch should fill the 256 CUs about
-//      twice, and segments should be long enough not to waste most of a 256-row tile;
+//   3: 256 x 256 on 8 waves - the fastest per tile (the tiles of an incomplete last round are
+//      cut along k, so few tiles are no problem), but segments should be long enough not to
+//      waste most of a 256-row tile;
 //   2: 128 x 256, 1: 64 x 256 on 4 waves for short segments.
 int pick_tile(const fine_shape& s, int n_ranks, int n_out, int bnc3) {
     int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
@@ -195,8 +285,8 @@ int pick_tile(const fine_shape& s, int n_ranks, int n_out, int bnc3) {
     // rank's ceil(P/G) rows span about E/G + 1 experts
     const double P = (double)s.T * s.K;
     const double seg_rows = (P / s.G) / ((double)s.E / s.G + 1.0);
-    const double tiles3 = std::ceil(P * n_ranks / s.G / 256.0) * std::ceil((double)n_out / bnc3);
-    if (seg_rows >= 384.0 && tiles3 >= 448.0) return 3;
+    (void)n_ranks; (void)n_out; (void)bnc3;
+    if (seg_rows >= 384.0) return 3;
     return seg_rows >= 96.0 ? 2 : 1;
 }
 
@@ -211,17 +301,17 @@ int run_ffn_tile(int tile, Args... args) {
 
 int launch_ffn_parts(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, const void* wg,
                      const void* wu, const void* wd, const int32_t* seg_off, void* h_buf, void* y_perm,
-                     void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, bool gemm1, bool gemm2,
-                     hipStream_t st) {
+                     void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, float* sk_partials, bool gemm1,
+                     bool gemm2, hipStream_t st) {
     const int t1 = pick_tile(s, rank_hi - rank_lo, s.f, 128), t2 = pick_tile(s, rank_hi - rank_lo, s.d, 256);
     if (t1 == t2 || !gemm1 || !gemm2)
         return run_ffn_tile(gemm1 ? t1 : t2, s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save,
-                            tiles, count, max_tiles, gemm1, gemm2, st);
+                            tiles, count, max_tiles, sk_partials, gemm1, gemm2, st);
     // different row tiles: the work list is rebuilt between the two GEMMs (same stream)
     FINE_TRY(run_ffn_tile(t1, s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles, count,
-                          max_tiles, true, false, st));
+                          max_tiles, sk_partials, true, false, st));
     return run_ffn_tile(t2, s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save, tiles, count,
-                        max_tiles, false, true, st);
+                        max_tiles, sk_partials, false, true, st);
 }
 
 int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm,
@@ -230,7 +320,7 @@ int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x
     const FfnWs L = ffn_ws_layout(s);
     return launch_ffn_parts(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, ws + L.h, y_perm, act_save,
                             reinterpret_cast<TileEntry*>(ws + L.tiles), reinterpret_cast<int32_t*>(ws + L.count),
-                            L.max_tiles, !(s.flags & FINE_FLAG_ONLY_GEMM2), !(s.flags & FINE_FLAG_ONLY_GEMM1), st);
+                            L.max_tiles, reinterpret_cast<float*>(ws + L.sk), !(s.flags & FINE_FLAG_ONLY_GEMM2), !(s.flags & FINE_FLAG_ONLY_GEMM1), st);
 }
 
 }  // namespace fine

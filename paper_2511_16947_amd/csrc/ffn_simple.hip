@@ -15,6 +15,7 @@ __global__ __launch_bounds__(256) void k_tile_map(const int32_t* __restrict__ se
     __shared__ int s_carry;
     const int tid = threadIdx.x;
     if (tid == 0) s_carry = 0;
+    count[kSkCounterOffset + tid] = 0;
     __syncthreads();
     const int nseg = (rank_hi - rank_lo) * E;
     for (int base = 0; base < nseg; base += 256) {
@@ -156,7 +157,8 @@ FfnWs ffn_ws_layout(const fine_shape& s) {
     size_t o = 0;
     w.h = o;     o = align_up(o + P * s.f * elem_size(s.dtype), 256);
     w.tiles = o; o = align_up(o + (size_t)w.max_tiles * sizeof(TileEntry), 256);
-    w.count = o; o = align_up(o + 256, 256);
+    w.count = o; o = align_up(o + kCountBytes, 256);
+    w.sk = o;    o = align_up(o + (s.dtype == FINE_BF16 ? kSkBytes : 0), 256);
     w.total = o;
     return w;
 }

@@ -102,13 +102,23 @@ def test_layer_forward_elementwise(cfg, tile):
     assert max_rel_err(to64(layer.y_perm), ref_y) <= tol
     assert max_rel_err(to64(layer.out), ref_out) <= tol
 
-    # per-rank calls give the same bits as the all-ranks call
+    # per-rank calls: the same rows; a launch cuts the k range of its last tiles by how many
+    # tiles it has, so fp32 sums may be taken in another order than in the all-ranks call
     y_all = layer.y_perm.clone()
     layer.y_perm.zero_()
     for r in range(cfg.G):
         layer.ffn(r)
     torch.cuda.synchronize()
-    assert torch.equal(layer.y_perm, y_all)
+    assert max_rel_err(to64(layer.y_perm), ref_y) <= tol
+    assert max_rel_err(to64(layer.y_perm), to64(y_all)) <= (1e-5 if cfg.dtype == "f32" else 2.0 ** -7)
+
+    # the same call again gives the same bits (partial sums are added in a fixed order)
+    y_first = layer.y_perm.clone()
+    layer.y_perm.zero_()
+    for r in range(cfg.G):
+        layer.ffn(r)
+    torch.cuda.synchronize()
+    assert torch.equal(layer.y_perm, y_first)
 
 
 def test_act_save_holds_the_preactivations():
