@@ -8,7 +8,7 @@
 //               e on every rank, ranks in ascending order: the replicas' gradients, which the
 //               paper sums with a data-parallel all-reduce, share one fp32 accumulator here)
 //   dX[token] = sum_k dXp[row(token, k)]
-#include "gemm_mfma.h"
+#include "gemm_w8.h"
 
 namespace fine {
 
@@ -18,27 +18,39 @@ using namespace mfma;
 
 // ---- dH = dY Wd^T with the SwiGLU backward epilogue -------------------------------------
 template <int WAVES_M, int WAVES_N, int WM, int WN>
-__global__ __launch_bounds__(256) void k_bwd_dh(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
-                                                const uint16_t* __restrict__ act, int d, int f,
-                                                uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
-                                                const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+__device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
+                                            const uint16_t* __restrict__ act, int d, int f,
+                                            uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
+                                            const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    constexpr bool W8 = WAVES_M * WAVES_N == 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int ntn = (f + BN - 1) / BN, ntm = *count, total = ntm * ntn;
-    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
     for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
         const TileEntry te = tiles[work % ntm];
         const int n0 = (work / ntm) * BN;
         const uint16_t* W = wd + (size_t)te.expert * f * d;
-        LoaderKC<BM> la;
-        la.init([&](int r) { return dy + (size_t)(te.row0 + min(r, te.rows - 1)) * d; });
-        LoaderKC<BN> lb;
-        lb.init([&](int n) { return W + (size_t)min(n0 + n, f - 1) * d; });
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
-        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(d / BK, smem, acc, la, lb, [&](int kt) {
-            return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)kt * BK, 0};
-        });
+        auto k_tile = [&](int kt) { return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)kt * BK, 0, 0}; };
+        if constexpr (W8) {
+            const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+            RowDmaOperand<WM> oa;
+            oa.init(dy + (size_t)te.row0 * d, [&](int r) { return (size_t)min(r, te.rows - 1) * d; },
+                    (uint32_t)((size_t)te.rows * d * 2), (wave / WAVES_N) * WM * 32);
+            RowDmaOperand<WN> ob;
+            ob.init(W, [&](int n) { return (size_t)min(n0 + n, f - 1) * d; }, (uint32_t)((size_t)f * d * 2),
+                    (wave % WAVES_N) * WN * 32);
+            const int nf = min(4, max(0, (te.rows - (wave / WAVES_N) * WM * 32 + 31) / 32));
+            if (te.rows == BM) k_loop8<false>(d / BK, smem, acc, oa, ob, k_tile);
+            else k_loop8<true>(d / BK, smem, acc, oa, ob, k_tile, nf);
+        } else {
+            LoaderKC<BM> la;
+            la.init([&](int r) { return dy + (size_t)(te.row0 + min(r, te.rows - 1)) * d; });
+            LoaderKC<BN> lb;
+            lb.init([&](int n) { return W + (size_t)min(n0 + n, f - 1) * d; });
+            k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(d / BK, smem, acc, la, lb, k_tile);
+        }
         constexpr int WMC = (BM * (BN * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
         stage_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(
             smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
@@ -74,37 +86,86 @@ __global__ __launch_bounds__(256) void k_bwd_dh(const uint16_t* __restrict__ dy,
     }
 }
 
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(256) void k_bwd_dh(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
+                                                const uint16_t* __restrict__ act, int d, int f,
+                                                uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
+                                                const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+    bwd_dh_body<WAVES_M, WAVES_N, WM, WN>(dy, wd, act, d, f, dact, h, tiles, count);
+}
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(512) void k_bwd_dh_w8(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
+                                                   const uint16_t* __restrict__ act, int d, int f,
+                                                   uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
+                                                   const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+    bwd_dh_body<WAVES_M, WAVES_N, WM, WN>(dy, wd, act, d, f, dact, h, tiles, count);
+}
+
 // ---- dXp = [dA | dB] [Wg | Wu]^T --------------------------------------------------------------
 template <int WAVES_M, int WAVES_N, int WM, int WN>
-__global__ __launch_bounds__(256) void k_bwd_dx(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
-                                                const uint16_t* __restrict__ wu, int d, int f,
-                                                uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
-                                                const int32_t* __restrict__ count) {
+__device__ __forceinline__ void bwd_dx_body(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
+                                            const uint16_t* __restrict__ wu, int d, int f,
+                                            uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
+                                            const int32_t* __restrict__ count) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    constexpr bool W8 = WAVES_M * WAVES_N == 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int ntn = (d + BN - 1) / BN, ntm = *count, total = ntm * ntn;
-    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int nkf = f / BK;
     for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
         const TileEntry te = tiles[work % ntm];
         const int n0 = (work / ntm) * BN;
         const uint16_t* Wg = wg + (size_t)te.expert * d * f;
         const uint16_t* Wu = wu + (size_t)te.expert * d * f;
-        LoaderKC<BM> la;
-        la.init([&](int r) { return dact + (size_t)(te.row0 + min(r, te.rows - 1)) * (2 * f); });
-        LoaderKC<BN> lb;     // pointers into Wg; the Wu half is reached through a constant offset
-        lb.init([&](int n) { return Wg + (size_t)min(n0 + n, d - 1) * f; });
+        // k runs over the f columns of dA with Wg_e, then over those of dB with Wu_e.  4 waves: the
+        // weight loader points into Wg and reaches Wu through a constant offset; 8 waves: the
+        // tile says which of the two sources it is in.
         const ptrdiff_t to_up = Wu - Wg;
+        auto k_tile = [&](int kt) {
+            if constexpr (W8)
+                return KTile{(ptrdiff_t)kt * BK, (ptrdiff_t)(kt < nkf ? kt : kt - nkf) * BK, 0, 0, kt < nkf ? 0 : 1};
+            else
+                return KTile{(ptrdiff_t)kt * BK, kt < nkf ? (ptrdiff_t)kt * BK : to_up + (ptrdiff_t)(kt - nkf) * BK, 0, 0, 0};
+        };
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
-        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(2 * nkf, smem, acc, la, lb, [&](int kt) {
-            return KTile{(ptrdiff_t)kt * BK, kt < nkf ? (ptrdiff_t)kt * BK : to_up + (ptrdiff_t)(kt - nkf) * BK, 0};
-        });
+        if constexpr (W8) {
+            const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+            RowDmaOperand<WM> oa;
+            oa.init(dact + (size_t)te.row0 * (2 * f), [&](int r) { return (size_t)min(r, te.rows - 1) * (2 * f); },
+                    (uint32_t)((size_t)te.rows * 2 * f * 2), (wave / WAVES_N) * WM * 32);
+            RowDmaOperand<WN> ob;
+            ob.init(Wg, [&](int n) { return (size_t)min(n0 + n, d - 1) * f; }, (uint32_t)((size_t)d * f * 2),
+                    (wave % WAVES_N) * WN * 32, Wu);
+            const int nf = min(4, max(0, (te.rows - (wave / WAVES_N) * WM * 32 + 31) / 32));
+            if (te.rows == BM) k_loop8<false>(2 * nkf, smem, acc, oa, ob, k_tile);
+            else k_loop8<true>(2 * nkf, smem, acc, oa, ob, k_tile, nf);
+        } else {
+            LoaderKC<BM> la;
+            la.init([&](int r) { return dact + (size_t)(te.row0 + min(r, te.rows - 1)) * (2 * f); });
+            LoaderKC<BN> lb;
+            lb.init([&](int n) { return Wg + (size_t)min(n0 + n, d - 1) * f; });
+            k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(2 * nkf, smem, acc, la, lb, k_tile);
+        }
         constexpr int WMC = (BM * (BN * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
         store_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(
             smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
             dxp, (size_t)d, te.row0, te.rows, n0, d);
     }
+}
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(256) void k_bwd_dx(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
+                                                const uint16_t* __restrict__ wu, int d, int f,
+                                                uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
+                                                const int32_t* __restrict__ count) {
+    bwd_dx_body<WAVES_M, WAVES_N, WM, WN>(dact, wg, wu, d, f, dxp, tiles, count);
+}
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(512) void k_bwd_dx_w8(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
+                                                   const uint16_t* __restrict__ wu, int d, int f,
+                                                   uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
+                                                   const int32_t* __restrict__ count) {
+    bwd_dx_body<WAVES_M, WAVES_N, WM, WN>(dact, wg, wu, d, f, dxp, tiles, count);
 }
 
 // ---- weight gradients: out[e][m][n] (+)= sum over the rows of expert e of A[row][m] * B[row][n] ----
@@ -115,11 +176,12 @@ struct WgradProblem {
 };
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
-__global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1, WgradProblem p2,
-                                               const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
+__device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, WgradProblem p2,
+                                           const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
+    constexpr bool W8 = WAVES_M * WAVES_N == 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)), wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int t0 = cdiv_dev(p0.M, BM) * cdiv_dev(p0.N, BN);
     const int t1 = cdiv_dev(p1.M, BM) * cdiv_dev(p1.N, BN);
     const int t2 = cdiv_dev(p2.M, BM) * cdiv_dev(p2.N, BN);
@@ -133,27 +195,38 @@ __global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1,
         else if (j >= t0) { p = p1; j -= t0; }
         const int ntm = cdiv_dev(p.M, BM);
         const int m0 = (j % ntm) * BM, n0 = (j / ntm) * BN;
-        LoaderMC<BM, true> la;
-        la.init([&](int r8) { return p.A + min(m0 + 8 * r8, p.M - 8); }, (size_t)p.lda);
-        LoaderMC<BN, true> lb;
-        lb.init([&](int r8) { return p.B + min(n0 + 8 * r8, p.N - 8); }, (size_t)p.ldb);
         // k-tiles: 64 rows at a time through the expert's segment on every rank, ascending
         int nk = 0;
         for (int g = 0; g < G; ++g)
             nk += (seg_off[(size_t)g * (E + 1) + e + 1] - seg_off[(size_t)g * (E + 1) + e] + BK - 1) / BK;
-        int cur_g = -1, cur_k = 0, cur_hi = 0;
-        f32x16 acc[WM][WN];
-        zero_acc<WM, WN>(acc);
-        k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, [&](int) {
+        int cur_g = -1, cur_k = 0, cur_lo = 0, cur_hi = 0;
+        auto k_tile = [&](int) {
             while (cur_k >= cur_hi) {          // advance to the next non-empty segment
                 ++cur_g;
-                cur_k = seg_off[(size_t)cur_g * (E + 1) + e];
+                cur_lo = cur_k = seg_off[(size_t)cur_g * (E + 1) + e];
                 cur_hi = seg_off[(size_t)cur_g * (E + 1) + e + 1];
             }
-            const KTile t{(ptrdiff_t)cur_k, (ptrdiff_t)cur_k, cur_hi};
+            const KTile t{(ptrdiff_t)cur_k, (ptrdiff_t)cur_k, cur_hi, cur_lo};
             cur_k += BK;
             return t;
-        });
+        };
+        f32x16 acc[WM][WN];
+        zero_acc<WM, WN>(acc);
+        if constexpr (W8) {
+            DmaOperand<WM> oa;
+            oa.init(p.A, p.A, [&](int pn, int c) { return min(m0 + 128 * pn + 8 * c, p.M - 8); }, (size_t)p.lda,
+                    [&](int f) { return 128 * wm + 32 * f; });
+            DmaOperand<WN> ob;
+            ob.init(p.B, p.B, [&](int pn, int c) { return min(n0 + 128 * pn + 8 * c, p.N - 8); }, (size_t)p.ldb,
+                    [&](int f) { return 64 * wn + 32 * f; });
+            k_loop8(nk, smem, acc, oa, ob, k_tile);
+        } else {
+            LoaderMC<BM, true> la;
+            la.init([&](int r8) { return p.A + min(m0 + 8 * r8, p.M - 8); }, (size_t)p.lda);
+            LoaderMC<BN, true> lb;
+            lb.init([&](int r8) { return p.B + min(n0 + 8 * r8, p.N - 8); }, (size_t)p.ldb);
+            k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, k_tile);
+        }
         float* out = p.out + (size_t)e * p.M * p.N;
         // each lane owns four consecutive columns of a row: 16-byte stores
         static_for<WM>([&](auto mi) {
@@ -180,14 +253,27 @@ __global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1,
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1, WgradProblem p2,
+                                               const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
+    wgrad_body<WAVES_M, WAVES_N, WM, WN>(p0, p1, p2, seg_off, E, G, accumulate);
+}
+template <int WAVES_M, int WAVES_N, int WM, int WN>
+__global__ __launch_bounds__(512) void k_wgrad_w8(WgradProblem p0, WgradProblem p1, WgradProblem p2,
+                                                  const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
+    wgrad_body<WAVES_M, WAVES_N, WM, WN>(p0, p1, p2, seg_off, E, G, accumulate);
+}
+
+template <int WAVES_M, int WAVES_N, int WM, int WN>
 int run_dgrad(const fine_shape& s, const uint16_t* dy, const uint16_t* act, const uint16_t* wg, const uint16_t* wu,
               const uint16_t* wd, const int32_t* seg_off, uint16_t* dact, uint16_t* h, uint16_t* dxp,
               TileEntry* tiles, int32_t* count, int max_tiles, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     FINE_TRY(launch_tile_map(s, seg_off, 0, s.G, BM, tiles, count, max_tiles, st));
     const size_t lds = (size_t)2 * (BM + BN) * 128;
-    auto k1 = k_bwd_dh<WAVES_M, WAVES_N, WM, WN>;
-    auto k2 = k_bwd_dx<WAVES_M, WAVES_N, WM, WN>;
+    constexpr bool W8 = WAVES_M * WAVES_N == 8;
+    constexpr int threads = WAVES_M * WAVES_N * 64;
+    auto k1 = [] { if constexpr (W8) return k_bwd_dh_w8<WAVES_M, WAVES_N, WM, WN>; else return k_bwd_dh<WAVES_M, WAVES_N, WM, WN>; }();
+    auto k2 = [] { if constexpr (W8) return k_bwd_dx_w8<WAVES_M, WAVES_N, WM, WN>; else return k_bwd_dx<WAVES_M, WAVES_N, WM, WN>; }();
     static bool attr_done = false;
     if (!attr_done) {
         FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k1, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
@@ -195,9 +281,9 @@ int run_dgrad(const fine_shape& s, const uint16_t* dy, const uint16_t* act, cons
         attr_done = true;
     }
     const int grid = 256 * ((lds <= 80 * 1024) ? 2 : 1);
-    hipLaunchKernelGGL(k1, dim3(grid), dim3(256), lds, st, dy, wd, act, s.d, s.f, dact, h, tiles, count);
+    hipLaunchKernelGGL(k1, dim3(grid), dim3(threads), lds, st, dy, wd, act, s.d, s.f, dact, h, tiles, count);
     FINE_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k2, dim3(grid), dim3(256), lds, st, dact, wg, wu, s.d, s.f, dxp, tiles, count);
+    hipLaunchKernelGGL(k2, dim3(grid), dim3(threads), lds, st, dact, wg, wu, s.d, s.f, dxp, tiles, count);
     FINE_LAUNCH_CHECK();
     return FINE_OK;
 }
@@ -207,7 +293,9 @@ int run_wgrad(const fine_shape& s, const uint16_t* x_perm, const uint16_t* dy, c
               const int32_t* seg_off, float* d_wg, float* d_wu, float* d_wd, int accumulate, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     const size_t lds = (size_t)2 * (BM + BN) * 128;
-    auto k = k_wgrad<WAVES_M, WAVES_N, WM, WN>;
+    constexpr bool W8 = WAVES_M * WAVES_N == 8;
+    constexpr int threads = WAVES_M * WAVES_N * 64;
+    auto k = [] { if constexpr (W8) return k_wgrad_w8<WAVES_M, WAVES_N, WM, WN>; else return k_wgrad<WAVES_M, WAVES_N, WM, WN>; }();
     static bool attr_done = false;
     if (!attr_done) {
         FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
@@ -217,7 +305,7 @@ int run_wgrad(const fine_shape& s, const uint16_t* x_perm, const uint16_t* dy, c
     WgradProblem pu{x_perm, s.d, s.d, dact + s.f, 2 * s.f, s.f, d_wu};
     WgradProblem pd{h, s.f, s.f, dy, s.d, s.d, d_wd};
     const int grid = 256 * ((lds <= 80 * 1024) ? 2 : 1);
-    hipLaunchKernelGGL(k, dim3(grid), dim3(256), lds, st, pg, pu, pd, seg_off, s.E, s.G, accumulate);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(threads), lds, st, pg, pu, pd, seg_off, s.E, s.G, accumulate);
     FINE_LAUNCH_CHECK();
     return FINE_OK;
 }
@@ -253,13 +341,13 @@ int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, 
 #define FINE_DGRAD(WAM, WAN, WMM, WNN)                                                                        \
     FINE_TRY((run_dgrad<WAM, WAN, WMM, WNN>(s, dy, act, (const uint16_t*)wg, (const uint16_t*)wu, (const uint16_t*)wd, \
                                             seg_off, dact, h, dxp, tiles, count, L.max_tiles, st)))
-    if (tile == 3) FINE_DGRAD(2, 2, 4, 4);
+    if (tile == 3) FINE_DGRAD(2, 4, 4, 2);
     else if (tile == 2) FINE_DGRAD(2, 2, 2, 4);
     else FINE_DGRAD(1, 4, 2, 2);
 #undef FINE_DGRAD
     // weight-gradient tiles span the weight matrices, not the segments
     if (s.d >= 256 && s.f >= 256 && tile != 1)
-        FINE_TRY((run_wgrad<2, 2, 4, 4>(s, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+        FINE_TRY((run_wgrad<2, 4, 4, 2>(s, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
     else
         FINE_TRY((run_wgrad<2, 2, 2, 2>(s, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
     FINE_TRY(launch_permute_bwd(s, dxp, row_of_pair, d_x, st));

@@ -49,24 +49,26 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
         const uint16_t* Bg = B0 + (size_t)te.expert * b_expert_stride;
         const uint16_t* Bu = (EPI == 0) ? B1 + (size_t)te.expert * b_expert_stride : nullptr;
         auto a_row = [&](int r) { return (size_t)min(r, te.rows - 1) * lda; };
-        auto k_tile = [&](int kt) { return KTile{(ptrdiff_t)(kb + kt) * BK, (ptrdiff_t)(kb + kt) * BK, Kd}; };
+        auto k_tile = [&](int kt) { return KTile{(ptrdiff_t)(kb + kt) * BK, (ptrdiff_t)(kb + kt) * BK, Kd, 0}; };
         if constexpr (W8) {
             const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-            RegOperand<WM> oa;
-            oa.init(A + (size_t)te.row0 * lda, a_row, (wave / WAVES_N) * WM * 32);
+            RowDmaOperand<WM> oa;
+            oa.init(A + (size_t)te.row0 * lda, a_row, (uint32_t)((size_t)te.rows * lda * 2), (wave / WAVES_N) * WM * 32);
             DmaOperand<WN> ob;
             const int wn = wave % WAVES_N;
-            const uint32_t w_bytes = (uint32_t)((size_t)Kd * N * 2);
             if constexpr (EPI == 0) {
                 // panel 0 = 128 gate columns, panel 1 = the matching up columns; a wave's two
                 // fragments are the same 32 columns of both
-                ob.init(Bg, Bu, w_bytes, [&](int, int c) { return min(n0 + 8 * c, N - 8); }, (size_t)N,
+                ob.init(Bg, Bu, [&](int, int c) { return min(n0 + 8 * c, N - 8); }, (size_t)N,
                         [&](int f) { return 128 * f + 32 * wn; });
             } else {
-                ob.init(Bg, Bg, w_bytes, [&](int p, int c) { return min(n0 + 128 * p + 8 * c, N - 8); }, (size_t)N,
+                ob.init(Bg, Bg, [&](int p, int c) { return min(n0 + 128 * p + 8 * c, N - 8); }, (size_t)N,
                         [&](int f) { return 64 * wn + 32 * f; });
             }
-            k_loop8(kn, smem, acc, oa, ob, k_tile);
+            // fragments of the wave that hold valid rows (the rest of a short last tile is skipped)
+            const int nf = min(4, max(0, (te.rows - (wave / WAVES_N) * WM * 32 + 31) / 32));
+            if (te.rows == BM) k_loop8<false, 4>(kn, smem, acc, oa, ob, k_tile);
+            else k_loop8<true, 4>(kn, smem, acc, oa, ob, k_tile, nf);
         } else {
             LoaderKC<BM> la;
             la.init([&](int r) { return A + (size_t)te.row0 * lda + a_row(r); });
@@ -247,7 +249,7 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     auto* h = reinterpret_cast<uint16_t*>(h_buf);
     FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
-    const size_t lds = (size_t)2 * (BM + BN) * 128;
+    const size_t lds = (WAVES_M * WAVES_N == 8) ? (size_t)w8_lds_bytes(true, 4) : (size_t)2 * (BM + BN) * 128;
     auto k1 = ffn_kernel<WAVES_M, WAVES_N, WM, WN, 0>();
     auto k2 = ffn_kernel<WAVES_M, WAVES_N, WM, WN, 1>();
     constexpr int threads = WAVES_M * WAVES_N * 64;

@@ -54,6 +54,8 @@ __device__ inline int lds_off(int row, int chunk) { return row * 128 + ((chunk ^
 struct KTile {
     ptrdiff_t a, b;
     int end;
+    int base;      // 8-wave ring operands: first source row of the segment the tile lies in
+    int sel;       // 8-wave row-DMA operand B: which of its two sources the tile is in
 };
 
 // ---------------------------------------------------------------------------

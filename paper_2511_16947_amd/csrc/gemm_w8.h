@@ -8,37 +8,39 @@
 // wave's MFMA runs.  The waves form a 2 x 4 grid, each owning 128 x 64 of the tile
 // (WM = 4, WN = 2 MFMA tiles): 128 accumulator registers per lane.
 //
-// How the operand tiles reach LDS depends on which way the source is contiguous:
+// Both operand tiles reach LDS by DMA (buffer_load_dwordx4 ... lds: 16 bytes per lane straight
+// into LDS, no registers, no LDS write instructions).  Measured: lane i's 16 bytes land at
+// LDS base + 16 i, a lane whose offset passes the descriptor's size writes zeros, and the
+// instruction's scalar offset takes part in that check.  Since the LDS side of such an
+// instruction is fixed, the XOR swizzles that keep the fragment reads free of bank conflicts
+// are applied by choosing WHICH global 16 bytes each lane fetches.  Two operand kinds:
 //
-//   RegOperand   source contiguous along k (activations [rows, k]; weights in the data
-//                gradients).  16-byte global loads into registers, 16-byte LDS writes one
-//                step later; LDS layout [row][64 k] with the swizzle of lds_off(), two
-//                buffers of 32 KB.  Four pieces per thread and k-tile of 64; a piece is
-//                reloaded right after it has been written, so one register set gives every
-//                load a full step (about 2000 cycles) before its data is needed.
+//   RowDmaOperand  source contiguous along k (activations [rows, k]; weights in the data
+//                gradients).  LDS layout [row][64 k] with the swizzle of lds_off(), two buffers
+//                of 32 KB; fragments are plain 16-byte LDS reads.  Four instructions per wave
+//                fill a 64-k tile, 8 rows of 128 bytes each.
 //
 //   DmaOperand   source contiguous along the tile's row index (weights [k, n] in the forward
-//                pass; both operands of the weight gradients).  buffer_load_dwordx4 ... lds
-//                copies 16 bytes per lane straight into LDS, no registers: the tile is kept
-//                as it lies in memory, [32 k][128 columns] per panel, two panels (16 KB) per
-//                stage, in a ring of four stages, and the MFMA fragments are read with the
-//                transposing LDS read ds_read_b64_tr_b16.  Measured: lane i's 16 bytes land
-//                at LDS base + 16 i (so a wave instruction fills four k-rows of 256 bytes), a
-//                lane whose offset passes the descriptor's size writes zeros (this is how rows
-//                beyond a ragged segment end become zero), and the scalar offset takes part in
-//                that check.  The XOR swizzle that keeps the fragment reads free of bank
-//                conflicts is applied by choosing WHICH global 16 bytes each lane fetches.
+//                pass; both operands of the weight gradients).  The tile is kept as it lies
+//                in memory, [32 k][128 columns] per panel, two panels (16 KB) per stage, in a
+//                ring of four stages, and the MFMA fragments are read with the transposing
+//                LDS read ds_read_b64_tr_b16.  A wave instruction fills four k-rows of 256
+//                bytes; rows beyond a ragged segment end come back as zeros through the
+//                descriptor's size.
 //                Lane layout of the transposing read (measured): in each group of 16 lanes,
 //                lane i receives element (i & 3) of the 8 bytes addressed by lanes
 //                (i >> 2), 4 + (i >> 2), 8 + (i >> 2), 12 + (i >> 2).  With lanes 4r .. 4r+3 of
 //                a group addressing 16 consecutive columns of k-row r, lane i ends up with
 //                column i of four consecutive k-rows - half of an MFMA operand fragment.
-//                (The global_load ... lds form is not used: the compiler treats it as a FLAT
-//                access and then drains vmcnt to zero at every dependency.)
+//
+// (The global_load ... lds form is not used: the compiler treats it as a FLAT access and then
+// drains vmcnt to zero at every dependency.  Measured alternatives that were no faster and
+// are gone: activations staged through registers with LDS writes one step later; a ring of
+// five stages.)
 //
 // The compiler does not order LDS reads after the DMA writes that produce their data; the
-// waits are written by hand: vmcnt counts DMA instructions and register loads in program
-// order, so "at most N outstanding" means the stage needed next has landed.
+// waits are written by hand: vmcnt counts DMA instructions in program order, so "at most N
+// outstanding" means the stage needed next has landed.
 #pragma once
 
 #include "gemm_mfma.h"
@@ -50,7 +52,10 @@ typedef short v4i16 __attribute__((ext_vector_type(4)));
 typedef short v8i16 __attribute__((ext_vector_type(8)));
 
 constexpr int kW8Threads = 512;
-constexpr int kW8Lds = 128 * 1024;          // operand A at 0, operand B at 64 KB
+constexpr int kW8OperandB = 64 * 1024;      // LDS: operand A at 0, operand B at 64 KB
+// bytes of LDS for the k-loop: A takes 64 KB either way (two buffers, or a ring of four
+// stages), B two buffers or a ring of `ring` stages
+constexpr int w8_lds_bytes(bool b_ring, int ring) { return kW8OperandB + (b_ring ? ring * 2 * 8192 : 64 * 1024); }
 constexpr int kStageBytes = 2 * 8192;        // one DMA stage: two panels of 32 k-rows x 128 bf16
 
 #define FINE_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
@@ -72,54 +77,15 @@ __device__ inline void block_barrier() {
 }
 
 // ---------------------------------------------------------------------------
-// NF = MFMA tiles of this operand per wave (4 for the M side, 2 for the N side).
+// Operands.  NF = MFMA tiles of this operand per wave (4 for the M side, 2 for the N side).
 // ---------------------------------------------------------------------------
-template <int NF>
-struct RegOperand {
-    static constexpr bool kDma = false;
-    const uint16_t* ptr;      // element (tile row 0, k = 0) + this thread's chunk
-    uint32_t off[4];          // element offset of tile row (tid >> 3) + 64 j from tile row 0
-    uint32_t lds[4];          // where piece j goes inside an LDS buffer
-    u32x4 reg[4];
-    int frow, half;           // fragment reads: first row of the wave's sub-tile + lane row; k half
-
-    // base: element (tile row 0, k = 0); row_off(r): element offset of tile row r from it
-    template <typename RowOff>
-    __device__ inline void init(const uint16_t* base, RowOff row_off, int wave_first) {
-        const int t = threadIdx.x;
-        ptr = base + (t & 7) * 8;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            off[j] = (uint32_t)row_off((t >> 3) + 64 * j);
-            lds[j] = (uint32_t)lds_off((t >> 3) + 64 * j, t & 7);
-        }
-        frow = wave_first + (t & 31);
-        half = (t & 63) >> 5;
-    }
-    template <int J>
-    __device__ inline void load_one(ptrdiff_t k) { reg[J] = *reinterpret_cast<const u32x4*>(ptr + k + off[J]); }
-    template <int J>
-    __device__ inline void store_one(char* buf) const {
-        // Written as an instruction: before a compiler-generated LDS store the compiler waits for
-        // every LDS-DMA instruction issued so far (it cannot tell the two apart in LDS), which
-        // would stall on the stage just requested.  It still waits for the load that produced
-        // reg[J]; completion of the write is covered by the lgkmcnt(0) before each barrier.
-        const uint32_t addr = (uint32_t)(uintptr_t)(buf) + lds[J];
-        asm volatile("ds_write_b128 %0, %1" ::"v"(addr), "v"(reg[J]) : "memory");
-    }
-    template <int T>
-    __device__ inline void issue(ptrdiff_t, char*) const {}      // (the other kind's interface: never called)
-    // fragment F (0 .. NF-1) of sub-step KK (0 .. 3) of the 64-k tile in `buf`
-    template <int KK, int F>
-    __device__ inline bf16x8 frag(const char* buf) const {
-        return *reinterpret_cast<const bf16x8*>(buf + lds_off(frow + 32 * F, 2 * KK + half));
-    }
-};
+enum OperandKind { kRing = 1, kRow = 2 };
 
 template <int NF>
 struct DmaOperand {
+    static constexpr int kKind = kRing;
     static constexpr bool kDma = true;
-    __amdgpu_buffer_rsrc_t rs[2];   // one buffer descriptor per panel (wave-uniform)
+    const uint16_t* src[2];         // element (source row 0, column 0) of the matrix behind each panel (wave-uniform)
     uint32_t voff[2];               // this lane's byte offset inside k-tile 0, per panel
     uint32_t ld2;                   // source row stride in bytes
     int wave;                       // wave-uniform
@@ -128,17 +94,15 @@ struct DmaOperand {
     // A stage is two panels of [32 k][128 tile columns] (8 KB each, k-rows of 256 bytes); one DMA
     // instruction fills four k-rows of one panel, wave w those starting at 4w.
     //   src0, src1   element (source row 0, column 0) of the matrix behind panel 0 / panel 1
-    //   bytes        size of that matrix from there on: a fetch that would pass it writes zeros
     //   col_off(p, c) source column of the 8 elements that make up columns 8c .. 8c+7 of panel p
     //   frag_col(f)  first tile column (0 .. 255, multiple of 32) of the wave's fragment f
     template <typename ColOff, typename FragCol>
-    __device__ inline void init(const uint16_t* src0, const uint16_t* src1, uint32_t bytes, ColOff col_off, size_t ld,
-                                FragCol frag_col) {
+    __device__ inline void init(const uint16_t* src0, const uint16_t* src1, ColOff col_off, size_t ld, FragCol frag_col) {
         const int lane = threadIdx.x & 63;
         wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
         ld2 = (uint32_t)(ld * 2);
-        rs[0] = __builtin_amdgcn_make_buffer_rsrc((void*)src0, 0, (int)bytes, 0x00020000);
-        rs[1] = __builtin_amdgcn_make_buffer_rsrc((void*)src1, 0, (int)bytes, 0x00020000);
+        src[0] = src0;
+        src[1] = src1;
         const int krow_w = 4 * wave + (lane >> 4);
         const int c = (lane & 15) ^ ((lane >> 4) << 2);          // the swizzle, applied on the global side
 #pragma unroll
@@ -152,16 +116,18 @@ struct DmaOperand {
             fr[f] = (uint32_t)((col >> 7) * 8192 + krow * 256 + ((((((col & 127) >> 3)) ^ x) + cl) << 4) + sub);
         }
     }
-    // panel T (0, 1) of the stage whose first source row is k0
+    // Panel T (0, 1) of the stage whose first source row is k0.  The buffer descriptor covers
+    // source rows [base, end): rows from `end` on arrive as zeros, and offsets stay small
+    // whatever the size of the whole array.
     template <int T>
-    __device__ inline void issue(ptrdiff_t k0, char* stage) const {
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs[T], FINE_LDS_PTR(stage + T * 8192 + wave * 1024), 16, voff[T],
-                                                 (uint32_t)k0 * ld2, 0, 0);
+    __device__ inline void issue(ptrdiff_t k0, int base, int end, char* stage) const {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(src[T] + (size_t)base * (ld2 / 2)), 0, (int)((uint32_t)(end - base) * ld2), 0x00020000);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, FINE_LDS_PTR(stage + T * 8192 + wave * 1024), 16, voff[T],
+                                                 (uint32_t)((int)k0 - base) * ld2, 0, 0);
     }
     template <int J>
-    __device__ inline void load_one(ptrdiff_t) {}                     // (the other kind's interface: never called)
-    template <int J>
-    __device__ inline void store_one(char*) const {}
+    __device__ inline void row_issue(ptrdiff_t, int, char*) const {}      // (the other kind's interface: never called)
     // fragment F of sub-step KK (0, 1) of the 32-k stage at `stage`
     template <int KK, int F>
     __device__ inline bf16x8 frag(const char* stage) const {
@@ -172,58 +138,121 @@ struct DmaOperand {
     }
 };
 
+// Source contiguous along k: LDS layout [row][64 k] with the swizzle of lds_off(), two
+// buffers of 32 KB, filled by four buffer_load ... lds instructions per
+// wave and 64-k tile: instruction j of wave w covers tile rows 64 j + 8 w .. + 7, lane i row
+// (i >> 3) of them and the LDS chunk (i & 7), for which it fetches the global chunk that the
+// swizzle puts there.  No registers, no LDS write instructions, no waits between barriers.
+template <int NF>
+struct RowDmaOperand {
+    static constexpr int kKind = kRow;
+    static constexpr bool kDma = true;
+    const uint16_t* src[2];   // element (tile row 0, k = 0) of the source, and of an alternative one (wave-uniform)
+    uint32_t bytes;           // valid bytes from there on (wave-uniform)
+    uint32_t voff[4];         // this lane's byte offset for instruction j at k = 0
+    int wave;
+    int frow, half;           // fragment reads: first row of the wave's sub-tile + lane row; k half
+
+    // base: element (tile row 0, k = 0); row_off(r): element offset of tile row r from it;
+    // bytes: from base to the end of the last row that may be fetched
+    template <typename RowOff>
+    __device__ inline void init(const uint16_t* base, RowOff row_off, uint32_t bytes_, int wave_first,
+                                const uint16_t* alt_base = nullptr) {
+        const int lane = threadIdx.x & 63;
+        wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+        src[0] = base;
+        src[1] = alt_base;
+        bytes = bytes_;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = 64 * j + 8 * wave + (lane >> 3);
+            const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+            voff[j] = (uint32_t)row_off(row) * 2u + (uint32_t)chunk * 16u;
+        }
+        frow = wave_first + (lane & 31);
+        half = lane >> 5;
+    }
+    // instruction J (0 .. 3) of the tile that starts at element k of every row of source `sel`
+    template <int J>
+    __device__ inline void row_issue(ptrdiff_t k, int sel, char* buf) const {
+        const __amdgpu_buffer_rsrc_t rs =
+            __builtin_amdgcn_make_buffer_rsrc((void*)(sel ? src[1] : src[0]), 0, (int)bytes, 0x00020000);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, FINE_LDS_PTR(buf + (64 * J + 8 * wave) * 128), 16, voff[J],
+                                                 (uint32_t)k * 2u, 0, 0);
+    }
+    template <int T>
+    __device__ inline void issue(ptrdiff_t, int, int, char*) const {}      // (the other kind's interface: never called)
+    template <int KK, int F>
+    __device__ inline bf16x8 frag(const char* buf) const {
+        return *reinterpret_cast<const bf16x8*>(buf + lds_off(frow + 32 * F, 2 * KK + half));
+    }
+};
+
 // KTile (shared with the 4-wave kernels) says where a k-tile starts: a / b are element offsets
-// along k for a RegOperand and source row numbers for a DmaOperand; `end` is not used here.
+// along k for a RowDmaOperand and source row numbers for a DmaOperand, whose
+// descriptor covers rows [base, end).
 
 // ---------------------------------------------------------------------------
 // Side operations of one 64-k tile, as a table: [half step P][slot 0..7] -> operation.
 // A half step is 2 sub-steps of 8 MFMAs per wave = 8 slots of two MFMAs; slots 0-3 come
-// before the half step's barrier, slots 4-7 after it.  LDS writes from registers must be
-// visible when the next tile's first fragments are read, which happens right after the
-// barrier of half step 1: so every register->LDS write sits before that barrier, each
-// followed (some time later) by the reload of its piece.
+// before the half step's barrier, slots 4-7 after it.  A ring operand requests its next stage
+// at the start of every half step.  A row operand's buffer is read for the last time before
+// the barrier of half step 1, so its refill (the tile after next) sits in slots 4-7 of that
+// half step and has two half steps to land.
 // ---------------------------------------------------------------------------
-enum SideKind { kNone = 0, kDmaA, kDmaB, kStoreA, kLoadA, kStoreB, kLoadB };
+enum SideKind { kNone = 0, kDmaA, kDmaB, kRowA, kRowB };
 struct SideOp {
     int kind, idx;
 };
-template <bool A_DMA, bool B_DMA>
+constexpr SideOp kNo{kNone, 0};
+// [half step][slot][up to two operations]; kA, kB = operand kinds
+template <int kA, int kB>
 struct Schedule;
 template <>
-struct Schedule<false, true> {      // activations through registers, weights by DMA (forward)
-    static constexpr SideOp op[2][8] = {
-        {{kDmaB, 0}, {kDmaB, 1}, {kStoreA, 0}, {kLoadA, 0}, {kStoreA, 1}, {kLoadA, 1}, {kStoreA, 2}, {kLoadA, 2}},
-        {{kDmaB, 0}, {kDmaB, 1}, {kStoreA, 3}, {kLoadA, 3}, {kNone, 0}, {kNone, 0}, {kNone, 0}, {kNone, 0}}};
+struct Schedule<kRow, kRing> {      // activations by row DMA, weights through the ring (forward)
+    static constexpr SideOp op[2][8][2] = {
+        {{{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}},
+        {{{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo},
+         {{kRowA, 0}, kNo}, {{kRowA, 1}, kNo}, {{kRowA, 2}, kNo}, {{kRowA, 3}, kNo}}};
 };
 template <>
-struct Schedule<false, false> {     // both through registers (data gradients)
-    static constexpr SideOp op[2][8] = {
-        {{kStoreA, 0}, {kLoadA, 0}, {kStoreB, 0}, {kLoadB, 0}, {kStoreA, 1}, {kLoadA, 1}, {kStoreB, 1}, {kLoadB, 1}},
-        {{kStoreA, 2}, {kStoreB, 2}, {kStoreA, 3}, {kStoreB, 3}, {kLoadA, 2}, {kLoadB, 2}, {kLoadA, 3}, {kLoadB, 3}}};
+struct Schedule<kRow, kRow> {       // both by row DMA (data gradients)
+    static constexpr SideOp op[2][8][2] = {
+        {{kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}},
+        {{kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo},
+         {{kRowA, 0}, {kRowB, 0}}, {{kRowA, 1}, {kRowB, 1}}, {{kRowA, 2}, {kRowB, 2}}, {{kRowA, 3}, {kRowB, 3}}}};
 };
 template <>
-struct Schedule<true, true> {       // both by DMA (weight gradients)
-    static constexpr SideOp op[2][8] = {
-        {{kDmaA, 0}, {kDmaA, 1}, {kDmaB, 0}, {kDmaB, 1}, {kNone, 0}, {kNone, 0}, {kNone, 0}, {kNone, 0}},
-        {{kDmaA, 0}, {kDmaA, 1}, {kDmaB, 0}, {kDmaB, 1}, {kNone, 0}, {kNone, 0}, {kNone, 0}, {kNone, 0}}};
+struct Schedule<kRing, kRing> {     // both through rings (weight gradients)
+    static constexpr SideOp op[2][8][2] = {
+        {{{kDmaA, 0}, kNo}, {{kDmaA, 1}, kNo}, {{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}},
+        {{{kDmaA, 0}, kNo}, {{kDmaA, 1}, kNo}, {{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}}};
 };
-constexpr bool is_vmem(SideOp o) { return o.kind == kDmaA || o.kind == kDmaB || o.kind == kLoadA || o.kind == kLoadB; }
-constexpr bool is_dma(SideOp o) { return o.kind == kDmaA || o.kind == kDmaB; }
-
-// How many vector memory instructions may still be outstanding at the barrier of half step P
-// when the DMA issued two half steps earlier (same P, previous tile) must have landed: those
-// issued after it in its own half step, all of the half step in between, and slots 0-3 of
-// this one.  vmcnt retires in order, so "at most that many outstanding" is the condition.
+constexpr bool is_dma(SideOp o) { return o.kind == kDmaA || o.kind == kDmaB || o.kind == kRowA || o.kind == kRowB; }
+constexpr bool is_vmem(SideOp o) { return is_dma(o); }
 template <typename S>
+constexpr int slot_vmem(int P, int i) { return (int)is_vmem(S::op[P][i][0]) + (int)is_vmem(S::op[P][i][1]); }
+template <typename S>
+constexpr bool slot_dma(int P, int i) { return is_dma(S::op[P][i][0]) || is_dma(S::op[P][i][1]); }
+
+// How many vector memory instructions may still be outstanding at the barrier of half step h
+// (parity P) when the DMA of stage h + 1 must have landed.  With a ring of RING stages that DMA
+// was issued RING - 2 half steps earlier; younger than it are the instructions issued after it
+// in its own half step, all of the half steps in between, and slots 0-3 of this one.  vmcnt
+// retires in order, so "at most that many outstanding" is the condition.
+template <typename S, int RING>
 constexpr int vm_allowed(int P) {
+    constexpr int D = RING - 2;
+    const int p0 = (P + D) & 1;               // parity of the half step that issued it
     int last = -1;
-    for (int i = 0; i < 8; ++i) if (is_dma(S::op[P][i])) last = i;
+    for (int i = 0; i < 8; ++i) if (slot_dma<S>(p0, i)) last = i;
     if (last < 0) return 63;                  // no DMA at all: nothing to wait for
     int n = 0;
-    for (int i = last + 1; i < 8; ++i) n += is_vmem(S::op[P][i]);
-    for (int i = 0; i < 8; ++i) n += is_vmem(S::op[P ^ 1][i]);
-    for (int i = 0; i < 4; ++i) n += is_vmem(S::op[P][i]);
-    return n;
+    for (int i = last + 1; i < 8; ++i) n += slot_vmem<S>(p0, i);
+    for (int j = 1; j < D; ++j)
+        for (int i = 0; i < 8; ++i) n += slot_vmem<S>((P + j) & 1, i);
+    for (int i = 0; i < 4; ++i) n += slot_vmem<S>(P, i);
+    return n < 63 ? n : 63;
 }
 
 struct Frags {
@@ -231,39 +260,40 @@ struct Frags {
 };
 
 // One half step (32 k-values).  On entry f0 holds the fragments of its first sub-step.
-//   a_src / b_src     what this half step computes on: LDS buffer (RegOperand) or ring stage
+//   a_src / b_src     what this half step computes on: LDS buffer (RowDmaOperand) or ring stage
 //   a_next / b_next   where the next half step's first fragments are (read after the barrier)
 //   a_dst / b_dst     what is filled meanwhile: the other LDS buffer / the free ring stage
 //   ka, kb            where the data to fetch starts (see KTile)
-template <int P, bool BARRIER, typename OA, typename OB>
+//   nf                (RAGGED_M only) how many of the wave's four 32-row fragments hold valid rows:
+//                     MFMAs and fragment reads of the others are skipped
+template <int P, bool BARRIER, bool RAGGED_M, int RING, typename OA, typename OB>
 __device__ inline void half_step8(const char* a_src, const char* b_src, const char* a_next, const char* b_next,
                                   char* a_dst, char* b_dst, f32x16 (&acc)[4][2], Frags& f0, Frags& f1, OA& oa,
-                                  OB& ob, ptrdiff_t ka, ptrdiff_t kb, int prof_kt = 0) {
+                                  OB& ob, ptrdiff_t ka, ptrdiff_t kb, int kbase, int kend, int ksel, int nf, int prof_kt = 0) {
     constexpr int WM = 4, WN = 2;
-    using S = Schedule<OA::kDma, OB::kDma>;
-    constexpr int KA1 = OA::kDma ? 1 : 2 * P + 1, KB1 = OB::kDma ? 1 : 2 * P + 1;       // second sub-step
-    constexpr int KA0 = OA::kDma ? 0 : (2 * P + 2) & 3, KB0 = OB::kDma ? 0 : (2 * P + 2) & 3;   // next first
+    using S = Schedule<OA::kKind, OB::kKind>;
+    constexpr bool ringA = OA::kKind == kRing, ringB = OB::kKind == kRing;
+    constexpr int KA1 = ringA ? 1 : 2 * P + 1, KB1 = ringB ? 1 : 2 * P + 1;                 // second sub-step
+    constexpr int KA0 = ringA ? 0 : (2 * P + 2) & 3, KB0 = ringB ? 0 : (2 * P + 2) & 3;     // next first
     auto side = [&](auto slot_c) {
 #ifndef FINE_DBG_NOSIDE
-        constexpr SideOp o = S::op[P][slot_c.value];
+        static_for<2>([&](auto which) {
+            constexpr SideOp o = S::op[P][slot_c.value][which.value];
 #ifdef FINE_DBG_NODMA
-        if constexpr (is_dma(o)) return;
+            if constexpr (is_dma(o)) return;
 #endif
-#ifdef FINE_DBG_NOREG
-        if constexpr (!is_dma(o)) return;
-#endif
-        if constexpr (o.kind == kDmaA) oa.template issue<o.idx>(ka, a_dst);
-        else if constexpr (o.kind == kDmaB) ob.template issue<o.idx>(kb, b_dst);
-        else if constexpr (o.kind == kStoreA) oa.template store_one<o.idx>(a_dst);
-        else if constexpr (o.kind == kLoadA) oa.template load_one<o.idx>(ka);
-        else if constexpr (o.kind == kStoreB) ob.template store_one<o.idx>(b_dst);
-        else if constexpr (o.kind == kLoadB) ob.template load_one<o.idx>(kb);
+            if constexpr (o.kind == kDmaA) oa.template issue<o.idx>(ka, kbase, kend, a_dst);
+            else if constexpr (o.kind == kDmaB) ob.template issue<o.idx>(kb, kbase, kend, b_dst);
+            else if constexpr (o.kind == kRowA) oa.template row_issue<o.idx>(ka, 0, a_dst);
+            else if constexpr (o.kind == kRowB) ob.template row_issue<o.idx>(kb, ksel, b_dst);
+        });
 #endif
     };
     auto mfma_pair = [&](auto j, const Frags& f) {
         static_for<2>([&](auto t) {
             constexpr int m = 2 * j.value + t.value;
             constexpr int mi = m / WN, ni = m % WN;
+            if (RAGGED_M && mi >= nf) return;
 #ifndef FINE_DBG_NOMFMA
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[mi][ni], 0, 0, 0);
 #else
@@ -282,6 +312,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
         } else if constexpr (slot_c.value <= 2) {
             static_for<2>([&](auto i) {
                 constexpr int fi = 2 * (slot_c.value - 1) + i.value;
+                if (RAGGED_M && fi >= nf) return;
                 f.a[fi] = oa.template frag<KA, fi>(a_from);
             });
         }
@@ -298,7 +329,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
     if (blockIdx.x == 0 && threadIdx.x == 0 && prof_kt < 64) g_prof[prof_kt * 8 + 1 + 4 * P] = clock64();
 #endif
     if constexpr (BARRIER) {
-        wait_vm_lgkm<vm_allowed<S>(P)>();
+        wait_vm_lgkm<vm_allowed<S, RING>(P)>();
         block_barrier();
     }
 #ifdef FINE_PROFILE_LOOP
@@ -323,60 +354,85 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
 // During half step h the DMA fills the slot of stage h + 3 (free since the barrier of h - 1)
 // and the registers write tile kt + 1 to the other LDS buffer and reload with tile kt + 2.
 // Fetches past the last tile repeat it; nobody reads them.
-template <typename OA, typename OB, typename Tile>
-__device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[4][2], OA& oa, OB& ob, Tile tile) {
-    static_assert(!(OA::kDma && !OB::kDma), "no schedule for this combination");
-    constexpr bool kAnyDma = OA::kDma || OB::kDma;
+// RAGGED_M: the wave computes only its first nf 32-row fragments (a row tile at the end of a
+// segment); the tile is still loaded whole.
+// RING: stages of a ring operand's ring (4 or 5; operand A's ring always has 4).
+template <bool RAGGED_M = false, int RING = 4, typename OA, typename OB, typename Tile>
+__device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[4][2], OA& oa, OB& ob, Tile tile, int nf = 4) {
+    constexpr int kA = OA::kKind, kB = OB::kKind;
+    constexpr bool kAnyRing = kA == kRing || kB == kRing;
+    static_assert(RING == 4 || (RING == 5 && kA != kRing), "ring depth");
     if (nk <= 0) return;
     char* base_a = smem;
-    char* base_b = smem + kW8Lds / 2;
+    char* base_b = smem + kW8OperandB;
     // where half step h of tile kt reads / where stage h or tile kt is written
-    auto a_at = [&](int kt, int h) { return base_a + (OA::kDma ? (h & 3) * kStageBytes : (kt & 1) * 32768); };
-    auto b_at = [&](int kt, int h) { return base_b + (OB::kDma ? (h & 3) * kStageBytes : (kt & 1) * 32768); };
-    auto clamped = [&](int kt) { return tile(min(kt, nk - 1)); };
+    auto a_at = [&](int kt, int h) { return base_a + (kA == kRing ? (h % RING) * kStageBytes : (kt & 1) * 32768); };
+    auto b_at = [&](int kt, int h) { return base_b + (kB == kRing ? (h % RING) * kStageBytes : (kt & 1) * 32768); };
+    // tile() is called once per k-tile, in order (it may keep state); past the last tile the
+    // last one is repeated
+    int fetched = 0;
+    KTile last_tile{0, 0, 0, 0, 0};
+    auto next_tile = [&]() {
+        if (fetched < nk) last_tile = tile(fetched);
+        ++fetched;
+        return last_tile;
+    };
 
-    // prologue: stages 0 .. 2, tile 0 into LDS, tile 1 into registers; everything lands
-    // before the first barrier, so the counts in the loop only ever concern the loop's own
-    // requests
+    // prologue: ring stages 0 .. RING-2, tile 0 into LDS, tile 1 into the other buffer (row
+    // DMA) or into registers; everything lands before the first barrier, so the counts in the
+    // loop only ever concern the loop's own requests
+    const KTile t0 = next_tile();
+    KTile n1 = next_tile();
     {
-        const KTile t0 = tile(0), t1 = clamped(1);
-        if constexpr (OA::kDma) {
-            oa.template issue<0>(t0.a, a_at(0, 0)); oa.template issue<1>(t0.a, a_at(0, 0));
-            oa.template issue<0>(t0.a + 32, a_at(0, 1)); oa.template issue<1>(t0.a + 32, a_at(0, 1));
-            oa.template issue<0>(t1.a, a_at(1, 2)); oa.template issue<1>(t1.a, a_at(1, 2));
+        static_for<RING - 1>([&](auto st) {          // stage st: half (st & 1) of tile st / 2
+            const KTile& t = st.value < 2 ? t0 : n1;
+            constexpr int half = (st.value & 1) * 32;
+            if constexpr (kA == kRing) {
+                oa.template issue<0>(t.a + half, t.base, t.end, a_at(0, st.value));
+                oa.template issue<1>(t.a + half, t.base, t.end, a_at(0, st.value));
+            }
+            if constexpr (kB == kRing) {
+                ob.template issue<0>(t.b + half, t.base, t.end, b_at(0, st.value));
+                ob.template issue<1>(t.b + half, t.base, t.end, b_at(0, st.value));
+            }
+        });
+        if constexpr (kA == kRow) {
+            static_for<4>([&](auto j) { oa.template row_issue<j.value>(t0.a, 0, a_at(0, 0)); });
+            static_for<4>([&](auto j) { oa.template row_issue<j.value>(n1.a, 0, a_at(1, 0)); });
         }
-        if constexpr (OB::kDma) {
-            ob.template issue<0>(t0.b, b_at(0, 0)); ob.template issue<1>(t0.b, b_at(0, 0));
-            ob.template issue<0>(t0.b + 32, b_at(0, 1)); ob.template issue<1>(t0.b + 32, b_at(0, 1));
-            ob.template issue<0>(t1.b, b_at(1, 2)); ob.template issue<1>(t1.b, b_at(1, 2));
-        }
-        if constexpr (!OA::kDma) {
-            static_for<4>([&](auto j) { oa.template load_one<j.value>(t0.a); });
-            static_for<4>([&](auto j) { oa.template store_one<j.value>(a_at(0, 0)); });
-            static_for<4>([&](auto j) { oa.template load_one<j.value>(t1.a); });
-        }
-        if constexpr (!OB::kDma) {
-            static_for<4>([&](auto j) { ob.template load_one<j.value>(t0.b); });
-            static_for<4>([&](auto j) { ob.template store_one<j.value>(b_at(0, 0)); });
-            static_for<4>([&](auto j) { ob.template load_one<j.value>(t1.b); });
+        if constexpr (kB == kRow) {
+            static_for<4>([&](auto j) { ob.template row_issue<j.value>(t0.b, t0.sel, b_at(0, 0)); });
+            static_for<4>([&](auto j) { ob.template row_issue<j.value>(n1.b, n1.sel, b_at(1, 0)); });
         }
         wait_vm_lgkm<0>();
         block_barrier();
     }
     Frags f0, f1;
-    static_for<4>([&](auto i) { f0.a[i.value] = oa.template frag<0, i.value>(a_at(0, 0)); });
+    static_for<4>([&](auto i) {
+        if (RAGGED_M && i.value >= nf) return;
+        f0.a[i.value] = oa.template frag<0, i.value>(a_at(0, 0));
+    });
     static_for<2>([&](auto i) { f0.b[i.value] = ob.template frag<0, i.value>(b_at(0, 0)); });
     for (int kt = 0; kt < nk; ++kt) {
-        const KTile n1 = clamped(kt + 1), n2 = clamped(kt + 2);
+        const KTile n2 = next_tile();          // tile kt + 2 (n1 = tile kt + 1)
         const int h = 2 * kt;
         FINE_PROF(0);
-        half_step8<0, kAnyDma>(a_at(kt, h), b_at(kt, h), a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + 3),
-                               b_at(kt + 1, h + 3), acc, f0, f1, oa, ob, OA::kDma ? n1.a + 32 : n2.a,
-                               OB::kDma ? n1.b + 32 : n2.b, kt);
+        // A ring operand's DMA in half step h requests stage h + RING - 1, i.e. tile
+        // kt + (P + RING - 1) / 2, half (P + RING - 1) % 2.  A row DMA (second half step, after its barrier) refills the
+        // buffer of tile kt, just read for the last time, with tile kt + 2.
+        const KTile& d0 = (RING == 4) ? n1 : n2;      // ring, P = 0
+        constexpr int d0_half = (RING == 4) ? 32 : 0, d1_half = (RING == 4) ? 0 : 32;
+        half_step8<0, kAnyRing, RAGGED_M, RING>(
+            a_at(kt, h), b_at(kt, h), a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + RING - 1),
+            b_at(kt + 1, h + RING - 1), acc, f0, f1, oa, ob, kA == kRing ? d0.a + d0_half : n2.a,
+            kB == kRing ? d0.b + d0_half : n2.b, d0.base, d0.end, 0, nf, kt);
         FINE_PROF(3);
-        half_step8<1, true>(a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + 2), b_at(kt + 1, h + 2),
-                            a_at(kt + 1, h + 4), b_at(kt + 1, h + 4), acc, f0, f1, oa, ob, n2.a, n2.b, kt);
+        half_step8<1, true, RAGGED_M, RING>(
+            a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + 2), b_at(kt + 1, h + 2),
+            kA == kRow ? a_at(kt, 0) : a_at(kt + 1, h + RING), kB == kRow ? b_at(kt, 0) : b_at(kt + 1, h + RING), acc, f0,
+            f1, oa, ob, kA == kRing ? n2.a + d1_half : n2.a, kB == kRing ? n2.b + d1_half : n2.b, n2.base, n2.end, n2.sel, nf, kt);
         FINE_PROF(7);
+        n1 = n2;
     }
     wait_vm_lgkm<0>();
     block_barrier();
