@@ -22,6 +22,12 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
 
+# Counter readings of the GEMM 1 kernel (mean KiB per launch over a default run of this file under
+# rocprofv3 --pmc; profiles/ffn_gemm1_w8_cfg2_mixtral_hbm_counters.md), scaled by what the same
+# counters read for --copy-calibration: FETCH_SIZE 0.5 per byte read, WRITE_SIZE 1.0 per byte written.
+GEMM1_TRAFFIC_BYTES = {"cfg2_mixtral": int(810751.0 * 1024 * 2.0 + 181197.2 * 1024 * 1.0)}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -158,22 +164,32 @@ def main():
     none = fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | fm.FLAG_ONLY_GEMM1 | fm.FLAG_ONLY_GEMM2)
     roofline = None
     if cfg.dtype == "bf16":
-        def burst_ms(fn, iters):      # one event pair around `iters` back-to-back calls: no launch gaps inside
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
+        only2 = fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | fm.FLAG_ONLY_GEMM2)
+
+        def sweep_ms(first, iters):
+            """Sweeps over the ranks as a step does them, each rank's call split in two (GEMM 1 alone, then
+            GEMM 2 alone: the same kernels in the same order, so every launch finds the caches as a step
+            leaves them); events bracket the first call only.  Nothing synchronises inside, so the
+            queue stays full and the events are GPU-side time stamps."""
+            evs = []
             for _ in range(iters):
-                fn()
-            b.record()
+                for r in range(s.G):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record(); st_ffn_rank(r, first); b.record()
+                    st_ffn_rank(r, only2)
+                    evs.append((a, b))
             torch.cuda.synchronize()
-            return a.elapsed_time(b) / iters
-        g1 = [burst_ms(lambda r=r: st_ffn_rank(r, only1), it) for r in range(s.G)]
-        tm = [burst_ms(lambda r=r: st_ffn_rank(r, none), it) for r in range(s.G)]
-        dur_ms = float(np.mean(g1) - np.mean(tm))                    # the work-list kernel that precedes it is subtracted
+            return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+        sweep_ms(only1, 1)
+        dur_ms = sweep_ms(only1, it) - sweep_ms(none, it)            # the work-list kernel that precedes it is subtracted
         flops_per_launch = 4.0 * float(rank_rows.mean()) * s.d * s.f  # rows of the rank x (gate + up) x 2
         achieved = flops_per_launch / (dur_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "k_ffn_gemm_w8<EPI=0> (X[Wg|Wu]+SwiGLU), one launch per rank",
                     "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                    "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+                    "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name) if args.ffn == "per_rank" else None,
+                    "traffic_unit": "bytes leaving the L2s per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
+                                    "factors from the 1 GiB copy calibration; see profiles/)",
                     "avg_launch_ms": round(dur_ms, 4), "flops_per_launch": flops_per_launch}
 
     es = 4 if cfg.dtype == "f32" else 2
