@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--no-backward", action="store_true")
     ap.add_argument("--detail-iters", type=int, default=10)
     ap.add_argument("--also-fused", action="store_true", help="also time one fine_grouped_ffn call for all ranks")
+    ap.add_argument("--tile", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="force the GEMM row tile (0 = the library's choice; 1 = 64, 2 = 128, 3 = 256 rows)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (the known-size kernel that HBM byte "
                          "counters are scaled by) and exit")
@@ -76,7 +78,7 @@ def main():
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
-    shape = fm.shape_of(cfg)
+    shape = fm.shape_of(cfg, fm.FLAG_LOCALITY | (args.tile << 8))
     s = shape
     topk_idx = torch.empty(s.T, s.K, dtype=torch.int32, device=dev)
     topk_w = torch.empty(s.T, s.K, dtype=torch.float32, device=dev)

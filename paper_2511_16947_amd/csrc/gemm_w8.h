@@ -308,6 +308,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
 #ifndef FINE_DBG_NOLDSREAD
         constexpr int KA = ka_c.value, KB = kb_c.value;
         if constexpr (slot_c.value == 0) {
+            if (RAGGED_M && nf == 0) return;      // a wave without valid rows reads nothing
             static_for<WN>([&](auto i) { f.b[i.value] = ob.template frag<KB, i.value>(b_from); });
         } else if constexpr (slot_c.value <= 2) {
             static_for<2>([&](auto i) {
@@ -412,7 +413,7 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[4][2], OA& oa, 
         if (RAGGED_M && i.value >= nf) return;
         f0.a[i.value] = oa.template frag<0, i.value>(a_at(0, 0));
     });
-    static_for<2>([&](auto i) { f0.b[i.value] = ob.template frag<0, i.value>(b_at(0, 0)); });
+    if (!(RAGGED_M && nf == 0)) static_for<2>([&](auto i) { f0.b[i.value] = ob.template frag<0, i.value>(b_at(0, 0)); });
     for (int kt = 0; kt < nk; ++kt) {
         const KTile n2 = next_tile();          // tile kt + 2 (n1 = tile kt + 1)
         const int h = 2 * kt;
