@@ -55,6 +55,38 @@ def test_sched_is_deterministic_across_runs():
         assert torch.equal(getattr(a, name), getattr(b, name))
 
 
+# ------------------------------------------------------------------ gate alone
+
+ROUTER_CASES = [
+    # T, d, E, K, dtype        which kernel takes it
+    (1000, 256, 8, 2, "bf16"),     # MFMA, waves split k; T not a multiple of 32
+    (33, 64, 32, 32, "bf16"),      # one k-step only (three waves idle), K = E at its limit
+    (257, 448, 64, 6, "bf16"),     # two expert tiles, k-steps not a multiple of 4
+    (300, 192, 128, 8, "bf16"),    # MFMA, block shares the slab; T not a multiple of 128
+    (129, 128, 256, 8, "bf16"),    # eight expert tiles
+    (64, 128, 24, 1, "bf16"),      # E a multiple of 8 but not of 32, K = 1
+    (200, 128, 12, 3, "bf16"),     # E not a multiple of 8: lane-per-expert kernel
+    (77, 50, 5, 2, "f32"),         # fp32
+]
+
+
+@pytest.mark.parametrize("case", ROUTER_CASES, ids=lambda c: "T%d_d%d_E%d_K%d_%s" % c)
+def test_router_topk(case):
+    T, d, E, K, dtype = case
+    cfg = wl.LayerConfig("router_case", T, d, 64, E, K, 1, dtype, 11, "scaled_z", 0.5)
+    inp = wl.make_inputs(cfg, DEV, with_weights=False)
+    shape = fm.shape_of(cfg)
+    idx = torch.full((T, K), -1, dtype=torch.int32, device=DEV)
+    w = torch.full((T, K), -1.0, dtype=torch.float32, device=DEV)
+    print("router case", case, flush=True)
+    fm.fine_topk(shape, inp.x, inp.w_router, inp.bias, idx, w)
+    torch.cuda.synchronize()
+    check_router(cfg, inp, idx, w)
+    got = idx.cpu().numpy()
+    assert got.min() >= 0 and got.max() < E
+    assert np.allclose(to64(w).sum(axis=1), 1.0, atol=1e-5)
+
+
 # ------------------------------------------------------------------ whole layer, small
 
 def small_cfgs():
