@@ -32,7 +32,8 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     constexpr int BNC = (EPI == 0) ? BN / 2 : BN;      // output columns per block
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
-    static_assert(WAVES_M * WAVES_N == 4 || (W8 && WAVES_N == 4 && WM == 4 && WN == 2), "4 waves, or 2 x 4 waves on 256 x 256");
+    static_assert(WAVES_M * WAVES_N == 4 || (W8 && WAVES_M == 2 && WAVES_N == 4 && (WM == 4 || WM == 2) && WN == 2),
+                  "4 waves, or 2 x 4 waves on 256 x 256 or 128 x 256");
     static_assert(EPI != 0 || WN % 2 == 0, "gate/up pairs");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -52,7 +53,7 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
         auto k_tile = [&](int kt) { return KTile{(ptrdiff_t)(kb + kt) * BK, (ptrdiff_t)(kb + kt) * BK, Kd, 0}; };
         if constexpr (W8) {
             const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-            RowDmaOperand<WM> oa;
+            RowDmaOperand<WM, BM> oa;
             oa.init(A + (size_t)te.row0 * lda, a_row, (uint32_t)((size_t)te.rows * lda * 2), (wave / WAVES_N) * WM * 32);
             DmaOperand<WN> ob;
             const int wn = wave % WAVES_N;
@@ -66,7 +67,7 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                         [&](int f) { return 64 * wn + 32 * f; });
             }
             // fragments of the wave that hold valid rows (the rest of a short last tile is skipped)
-            const int nf = min(4, max(0, (te.rows - (wave / WAVES_N) * WM * 32 + 31) / 32));
+            const int nf = min(WM, max(0, (te.rows - (wave / WAVES_N) * WM * 32 + 31) / 32));
             if (te.rows == BM) k_loop8<false, 4>(kn, smem, acc, oa, ob, k_tile);
             else k_loop8<true, 4>(kn, smem, acc, oa, ob, k_tile, nf);
         } else {
@@ -127,7 +128,13 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     // block order - the same sum whoever it is - and runs the epilogue.  Nobody waits.
     __shared__ int s_last;
     const int nblk = gridDim.x, bid = xcd_contiguous_id();
-    const int full = W8 ? (total / nblk) * nblk : total;
+    // the cut pays when the k-steps it saves (the last round would take nk, the cut takes
+    // rest * nk / nblk) outweigh writing, re-reading and adding up partial tiles; measured on three
+    // workloads, the break-even is about 16 WM steps (GEMM 2 of a rank with 128 tiles and 224 steps
+    // gains a lot, half a round of 64-step tiles gains nothing, short k-loops lose)
+    const int whole_rounds = (total / nblk) * nblk;
+    const bool cut = W8 && (long long)nk * (nblk - (total - whole_rounds)) > (long long)16 * WM * nblk;
+    const int full = cut ? whole_rounds : total;
     const int rest = total - full;
     const int per = (rest * nk + nblk - 1) / nblk;
     int32_t* counters = count + kSkCounterOffset;
@@ -137,8 +144,12 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     // invalidate (a fence) is needed, which would cost every block on the XCD its cached
     // operand tiles.
     auto slot_ptr = [&](int slot, int j) {
-        return reinterpret_cast<uint64_t*>(sk_partials) + ((size_t)slot * 64 + j) * (WAVES_M * WAVES_N * 64) + threadIdx.x;
+        return reinterpret_cast<uint64_t*>(sk_partials) + ((size_t)slot * (WM * WN * 8) + j) * (WAVES_M * WAVES_N * 64) + threadIdx.x;
     };
+#ifdef FINE_PROFILE_LOOP
+    const unsigned long long blk_w0 = wall_clock64(), blk_c0 = clock64();
+    int blk_tiles = 0;
+#endif
     int next_whole = bid, u = bid * per;
     const int u1 = min(rest * nk, u + per);
     for (;;) {
@@ -210,7 +221,18 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
         if (finish) epilogue(work);
         FINE_PROF_TILE(2);
         FINE_PROF_TILE(6);
+#ifdef FINE_PROFILE_LOOP
+        ++blk_tiles;
+#endif
     }
+#ifdef FINE_PROFILE_LOOP
+    if (threadIdx.x == 0 && blockIdx.x < 256) {
+        g_prof[1024 + blockIdx.x * 4 + 0] = blk_w0;
+        g_prof[1024 + blockIdx.x * 4 + 1] = wall_clock64();
+        g_prof[1024 + blockIdx.x * 4 + 2] = clock64() - blk_c0;
+        g_prof[1024 + blockIdx.x * 4 + 3] = blk_tiles;
+    }
+#endif
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
@@ -279,7 +301,8 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
 //   3: 256 x 256 on 8 waves - the fastest per tile (the tiles of an incomplete last round are
 //      cut along k, so few tiles are no problem), but segments should be long enough not to
 //      waste most of a 256-row tile;
-//   2: 128 x 256, 1: 64 x 256 on 4 waves for short segments.
+//   2: 128 x 256 on 8 waves (same machinery, half the rows), 1: 64 x 256 on 4 waves for short
+//      segments.
 int pick_tile(const fine_shape& s, int n_ranks, int n_out, int bnc3) {
     int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
     if (tile != 0) return tile;
@@ -295,7 +318,7 @@ int pick_tile(const fine_shape& s, int n_ranks, int n_out, int bnc3) {
 template <typename... Args>
 int run_ffn_tile(int tile, Args... args) {
     if (tile == 3) return run_ffn<2, 4, 4, 2>(args...);
-    if (tile == 2) return run_ffn<2, 2, 2, 4>(args...);
+    if (tile == 2) return run_ffn<2, 4, 2, 2>(args...);
     return run_ffn<1, 4, 2, 2>(args...);
 }
 
@@ -329,6 +352,6 @@ int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x
 
 #ifdef FINE_PROFILE_LOOP
 extern "C" __attribute__((visibility("default"))) int fine_debug_prof(unsigned long long* host_out) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(fine::mfma::g_prof), sizeof(unsigned long long) * 128 * 8);
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(fine::mfma::g_prof), sizeof(unsigned long long) * (128 * 8 + 1024));
 }
 #endif

@@ -230,7 +230,7 @@ constexpr int share_begin(int slot, int total, int slots) { return (total * slot
 
 #ifdef FINE_PROFILE_LOOP
 // scratch instrumentation (never in the shipped build): cycle stamps of block 0, wave 0
-static __device__ unsigned long long g_prof[128 * 8];
+static __device__ unsigned long long g_prof[128 * 8 + 1024];    // + per block: start, end (wall clock), clock64 span, tiles
 #define FINE_PROF(slot)                                                                          \
     do {                                                                                         \
         if (blockIdx.x == 0 && threadIdx.x == 0 && kt < 64) g_prof[kt * 8 + (slot)] = clock64(); \

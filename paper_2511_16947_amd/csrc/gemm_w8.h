@@ -85,6 +85,7 @@ template <int NF>
 struct DmaOperand {
     static constexpr int kKind = kRing;
     static constexpr bool kDma = true;
+    static constexpr int kInstr = 2, kBufBytes = kStageBytes;      // per stage
     const uint16_t* src[2];         // element (source row 0, column 0) of the matrix behind each panel (wave-uniform)
     uint32_t voff[2];               // this lane's byte offset inside k-tile 0, per panel
     uint32_t ld2;                   // source row stride in bytes
@@ -139,17 +140,19 @@ struct DmaOperand {
 };
 
 // Source contiguous along k: LDS layout [row][64 k] with the swizzle of lds_off(), two
-// buffers of 32 KB, filled by four buffer_load ... lds instructions per
+// buffers of ROWS x 128 bytes, filled by ROWS / 64 buffer_load ... lds instructions per
 // wave and 64-k tile: instruction j of wave w covers tile rows 64 j + 8 w .. + 7, lane i row
 // (i >> 3) of them and the LDS chunk (i & 7), for which it fetches the global chunk that the
 // swizzle puts there.  No registers, no LDS write instructions, no waits between barriers.
-template <int NF>
+template <int NF, int ROWS = 256>
 struct RowDmaOperand {
     static constexpr int kKind = kRow;
+    static constexpr int kInstr = ROWS / 64;          // DMA instructions per wave and tile
+    static constexpr int kBufBytes = ROWS * 128;
     static constexpr bool kDma = true;
     const uint16_t* src[2];   // element (tile row 0, k = 0) of the source, and of an alternative one (wave-uniform)
     uint32_t bytes;           // valid bytes from there on (wave-uniform)
-    uint32_t voff[4];         // this lane's byte offset for instruction j at k = 0
+    uint32_t voff[4];         // this lane's byte offset for instruction j (< kInstr) at k = 0
     int wave;
     int frow, half;           // fragment reads: first row of the wave's sub-tile + lane row; k half
 
@@ -164,7 +167,7 @@ struct RowDmaOperand {
         src[1] = alt_base;
         bytes = bytes_;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < kInstr; ++j) {
             const int row = 64 * j + 8 * wave + (lane >> 3);
             const int chunk = (lane & 7) ^ ((row >> 1) & 7);
             voff[j] = (uint32_t)row_off(row) * 2u + (uint32_t)chunk * 16u;
@@ -205,25 +208,36 @@ struct SideOp {
     int kind, idx;
 };
 constexpr SideOp kNo{kNone, 0};
-// [half step][slot][up to two operations]; kA, kB = operand kinds
-template <int kA, int kB>
+// [half step][slot][up to two operations]; kA, kB = operand kinds; WM = 32-row fragments per wave
+// (a sub-step has WM slots, a half step 2 WM)
+template <int kA, int kB, int WM>
 struct Schedule;
 template <>
-struct Schedule<kRow, kRing> {      // activations by row DMA, weights through the ring (forward)
+struct Schedule<kRow, kRing, 2> {   // forward, 128-row tile: two slots per sub-step
+    static constexpr int kSlots = 4;
+    static constexpr SideOp op[2][4][2] = {
+        {{{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo}},
+        {{{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {{kRowA, 0}, kNo}, {{kRowA, 1}, kNo}}};
+};
+template <>
+struct Schedule<kRow, kRing, 4> {   // activations by row DMA, weights through the ring (forward)
+    static constexpr int kSlots = 8;
     static constexpr SideOp op[2][8][2] = {
         {{{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}},
         {{{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo},
          {{kRowA, 0}, kNo}, {{kRowA, 1}, kNo}, {{kRowA, 2}, kNo}, {{kRowA, 3}, kNo}}};
 };
 template <>
-struct Schedule<kRow, kRow> {       // both by row DMA (data gradients)
+struct Schedule<kRow, kRow, 4> {    // both by row DMA (data gradients)
+    static constexpr int kSlots = 8;
     static constexpr SideOp op[2][8][2] = {
         {{kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}},
         {{kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo},
          {{kRowA, 0}, {kRowB, 0}}, {{kRowA, 1}, {kRowB, 1}}, {{kRowA, 2}, {kRowB, 2}}, {{kRowA, 3}, {kRowB, 3}}}};
 };
 template <>
-struct Schedule<kRing, kRing> {     // both through rings (weight gradients)
+struct Schedule<kRing, kRing, 4> {  // both through rings (weight gradients)
+    static constexpr int kSlots = 8;
     static constexpr SideOp op[2][8][2] = {
         {{{kDmaA, 0}, kNo}, {{kDmaA, 1}, kNo}, {{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}},
         {{{kDmaA, 0}, kNo}, {{kDmaA, 1}, kNo}, {{kDmaB, 0}, kNo}, {{kDmaB, 1}, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}, {kNo, kNo}}};
@@ -238,25 +252,26 @@ constexpr bool slot_dma(int P, int i) { return is_dma(S::op[P][i][0]) || is_dma(
 // How many vector memory instructions may still be outstanding at the barrier of half step h
 // (parity P) when the DMA of stage h + 1 must have landed.  With a ring of RING stages that DMA
 // was issued RING - 2 half steps earlier; younger than it are the instructions issued after it
-// in its own half step, all of the half steps in between, and slots 0-3 of this one.  vmcnt
+// in its own half step, all of the half steps in between, and the first half of this one.  vmcnt
 // retires in order, so "at most that many outstanding" is the condition.
 template <typename S, int RING>
 constexpr int vm_allowed(int P) {
     constexpr int D = RING - 2;
     const int p0 = (P + D) & 1;               // parity of the half step that issued it
     int last = -1;
-    for (int i = 0; i < 8; ++i) if (slot_dma<S>(p0, i)) last = i;
+    for (int i = 0; i < S::kSlots; ++i) if (slot_dma<S>(p0, i)) last = i;
     if (last < 0) return 63;                  // no DMA at all: nothing to wait for
     int n = 0;
-    for (int i = last + 1; i < 8; ++i) n += slot_vmem<S>(p0, i);
+    for (int i = last + 1; i < S::kSlots; ++i) n += slot_vmem<S>(p0, i);
     for (int j = 1; j < D; ++j)
-        for (int i = 0; i < 8; ++i) n += slot_vmem<S>((P + j) & 1, i);
-    for (int i = 0; i < 4; ++i) n += slot_vmem<S>(P, i);
+        for (int i = 0; i < S::kSlots; ++i) n += slot_vmem<S>((P + j) & 1, i);
+    for (int i = 0; i < S::kSlots / 2; ++i) n += slot_vmem<S>(P, i);
     return n < 63 ? n : 63;
 }
 
+template <int WM>
 struct Frags {
-    bf16x8 a[4], b[2];
+    bf16x8 a[WM], b[2];
 };
 
 // One half step (32 k-values).  On entry f0 holds the fragments of its first sub-step.
@@ -266,12 +281,12 @@ struct Frags {
 //   ka, kb            where the data to fetch starts (see KTile)
 //   nf                (RAGGED_M only) how many of the wave's four 32-row fragments hold valid rows:
 //                     MFMAs and fragment reads of the others are skipped
-template <int P, bool BARRIER, bool RAGGED_M, int RING, typename OA, typename OB>
+template <int P, bool BARRIER, bool RAGGED_M, int RING, int WM, typename OA, typename OB>
 __device__ inline void half_step8(const char* a_src, const char* b_src, const char* a_next, const char* b_next,
-                                  char* a_dst, char* b_dst, f32x16 (&acc)[4][2], Frags& f0, Frags& f1, OA& oa,
+                                  char* a_dst, char* b_dst, f32x16 (&acc)[WM][2], Frags<WM>& f0, Frags<WM>& f1, OA& oa,
                                   OB& ob, ptrdiff_t ka, ptrdiff_t kb, int kbase, int kend, int ksel, int nf, int prof_kt = 0) {
-    constexpr int WM = 4, WN = 2;
-    using S = Schedule<OA::kKind, OB::kKind>;
+    constexpr int WN = 2;
+    using S = Schedule<OA::kKind, OB::kKind, WM>;
     constexpr bool ringA = OA::kKind == kRing, ringB = OB::kKind == kRing;
     constexpr int KA1 = ringA ? 1 : 2 * P + 1, KB1 = ringB ? 1 : 2 * P + 1;                 // second sub-step
     constexpr int KA0 = ringA ? 0 : (2 * P + 2) & 3, KB0 = ringB ? 0 : (2 * P + 2) & 3;     // next first
@@ -289,7 +304,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
         });
 #endif
     };
-    auto mfma_pair = [&](auto j, const Frags& f) {
+    auto mfma_pair = [&](auto j, const Frags<WM>& f) {
         static_for<2>([&](auto t) {
             constexpr int m = 2 * j.value + t.value;
             constexpr int mi = m / WN, ni = m % WN;
@@ -304,13 +319,13 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
     // Fragment reads are spread over the slots (B fragments in slot 0, A fragments in slots 1
     // and 2): issued in one burst they would keep the MFMA pipe idle for their issue time,
     // since both waves of a SIMD reach that point together.
-    auto reads = [&](auto slot_c, Frags& f, auto ka_c, auto kb_c, const char* a_from, const char* b_from) {
+    auto reads = [&](auto slot_c, Frags<WM>& f, auto ka_c, auto kb_c, const char* a_from, const char* b_from) {
 #ifndef FINE_DBG_NOLDSREAD
         constexpr int KA = ka_c.value, KB = kb_c.value;
         if constexpr (slot_c.value == 0) {
             if (RAGGED_M && nf == 0) return;      // a wave without valid rows reads nothing
             static_for<WN>([&](auto i) { f.b[i.value] = ob.template frag<KB, i.value>(b_from); });
-        } else if constexpr (slot_c.value <= 2) {
+        } else if constexpr (2 * (slot_c.value - 1) < WM) {
             static_for<2>([&](auto i) {
                 constexpr int fi = 2 * (slot_c.value - 1) + i.value;
                 if (RAGGED_M && fi >= nf) return;
@@ -320,7 +335,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
 #endif
     };
     // first sub-step: MFMAs on f0 while the second sub-step's fragments arrive in f1
-    static_for<4>([&](auto j) {
+    static_for<WM>([&](auto j) {
         reads(j, f1, IntC<KA1>{}, IntC<KB1>{}, a_src, b_src);
         mfma_pair(j, f0);
         side(IntC<j.value>{});
@@ -337,10 +352,10 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
     if (blockIdx.x == 0 && threadIdx.x == 0 && prof_kt < 64) g_prof[prof_kt * 8 + 2 + 4 * P] = clock64();
 #endif
     // second sub-step: MFMAs on f1 while the next half step's first fragments arrive in f0
-    static_for<4>([&](auto j) {
+    static_for<WM>([&](auto j) {
         reads(j, f0, IntC<KA0>{}, IntC<KB0>{}, a_next, b_next);
         mfma_pair(j, f1);
-        side(IntC<4 + j.value>{});
+        side(IntC<WM + j.value>{});
         __builtin_amdgcn_sched_barrier(0);
     });
 }
@@ -358,8 +373,8 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
 // RAGGED_M: the wave computes only its first nf 32-row fragments (a row tile at the end of a
 // segment); the tile is still loaded whole.
 // RING: stages of a ring operand's ring (4 or 5; operand A's ring always has 4).
-template <bool RAGGED_M = false, int RING = 4, typename OA, typename OB, typename Tile>
-__device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[4][2], OA& oa, OB& ob, Tile tile, int nf = 4) {
+template <bool RAGGED_M = false, int RING = 4, int WM, typename OA, typename OB, typename Tile>
+__device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[WM][2], OA& oa, OB& ob, Tile tile, int nf = WM) {
     constexpr int kA = OA::kKind, kB = OB::kKind;
     constexpr bool kAnyRing = kA == kRing || kB == kRing;
     static_assert(RING == 4 || (RING == 5 && kA != kRing), "ring depth");
@@ -367,8 +382,8 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[4][2], OA& oa, 
     char* base_a = smem;
     char* base_b = smem + kW8OperandB;
     // where half step h of tile kt reads / where stage h or tile kt is written
-    auto a_at = [&](int kt, int h) { return base_a + (kA == kRing ? (h % RING) * kStageBytes : (kt & 1) * 32768); };
-    auto b_at = [&](int kt, int h) { return base_b + (kB == kRing ? (h % RING) * kStageBytes : (kt & 1) * 32768); };
+    auto a_at = [&](int kt, int h) { return base_a + (kA == kRing ? h % RING : kt & 1) * OA::kBufBytes; };
+    auto b_at = [&](int kt, int h) { return base_b + (kB == kRing ? h % RING : kt & 1) * OB::kBufBytes; };
     // tile() is called once per k-tile, in order (it may keep state); past the last tile the
     // last one is repeated
     int fetched = 0;
@@ -398,18 +413,18 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[4][2], OA& oa, 
             }
         });
         if constexpr (kA == kRow) {
-            static_for<4>([&](auto j) { oa.template row_issue<j.value>(t0.a, 0, a_at(0, 0)); });
-            static_for<4>([&](auto j) { oa.template row_issue<j.value>(n1.a, 0, a_at(1, 0)); });
+            static_for<OA::kInstr>([&](auto j) { oa.template row_issue<j.value>(t0.a, 0, a_at(0, 0)); });
+            static_for<OA::kInstr>([&](auto j) { oa.template row_issue<j.value>(n1.a, 0, a_at(1, 0)); });
         }
         if constexpr (kB == kRow) {
-            static_for<4>([&](auto j) { ob.template row_issue<j.value>(t0.b, t0.sel, b_at(0, 0)); });
-            static_for<4>([&](auto j) { ob.template row_issue<j.value>(n1.b, n1.sel, b_at(1, 0)); });
+            static_for<OB::kInstr>([&](auto j) { ob.template row_issue<j.value>(t0.b, t0.sel, b_at(0, 0)); });
+            static_for<OB::kInstr>([&](auto j) { ob.template row_issue<j.value>(n1.b, n1.sel, b_at(1, 0)); });
         }
         wait_vm_lgkm<0>();
         block_barrier();
     }
-    Frags f0, f1;
-    static_for<4>([&](auto i) {
+    Frags<WM> f0, f1;
+    static_for<WM>([&](auto i) {
         if (RAGGED_M && i.value >= nf) return;
         f0.a[i.value] = oa.template frag<0, i.value>(a_at(0, 0));
     });
@@ -423,12 +438,12 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[4][2], OA& oa, 
         // buffer of tile kt, just read for the last time, with tile kt + 2.
         const KTile& d0 = (RING == 4) ? n1 : n2;      // ring, P = 0
         constexpr int d0_half = (RING == 4) ? 32 : 0, d1_half = (RING == 4) ? 0 : 32;
-        half_step8<0, kAnyRing, RAGGED_M, RING>(
+        half_step8<0, kAnyRing, RAGGED_M, RING, WM>(
             a_at(kt, h), b_at(kt, h), a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + RING - 1),
             b_at(kt + 1, h + RING - 1), acc, f0, f1, oa, ob, kA == kRing ? d0.a + d0_half : n2.a,
             kB == kRing ? d0.b + d0_half : n2.b, d0.base, d0.end, 0, nf, kt);
         FINE_PROF(3);
-        half_step8<1, true, RAGGED_M, RING>(
+        half_step8<1, true, RAGGED_M, RING, WM>(
             a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + 2), b_at(kt + 1, h + 2),
             kA == kRow ? a_at(kt, 0) : a_at(kt + 1, h + RING), kB == kRow ? b_at(kt, 0) : b_at(kt + 1, h + RING), acc, f0,
             f1, oa, ob, kA == kRing ? n2.a + d1_half : n2.a, kB == kRing ? n2.b + d1_half : n2.b, n2.base, n2.end, n2.sel, nf, kt);

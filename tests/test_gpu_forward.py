@@ -153,6 +153,29 @@ def test_layer_forward_elementwise(cfg, tile):
     assert torch.equal(layer.y_perm, y_first)
 
 
+@pytest.mark.parametrize("tile", [2, 3])
+def test_tiles_cut_along_k(tile):
+    """Few tiles and a long k range in GEMM 2 (f = 80 x 64): the launch cuts every tile's k range
+    over many blocks and adds the partial sums up.  Element by element against the oracle, and
+    bit-stable from run to run."""
+    cfg = wl.LayerConfig("k_cut", 256, 256, 5120, 2, 2, 1, "bf16", 7, "scaled_z", 0.5)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+    print("k-cut case tile", tile, flush=True)
+    layer.forward()
+    idx = layer.topk_idx.cpu().numpy()
+    want = sched.schedule(idx, cfg.E, cfg.G)
+    weights_of = weights_of_factory(inp)
+    ref_y = moe.grouped_ffn(moe.permute(to64(inp.x), want["pair_of_row"], cfg.K), want["seg_off"], weights_of)
+    assert max_rel_err(to64(layer.y_perm), ref_y) <= tol_for(cfg)
+    first = layer.y_perm.clone()
+    for _ in range(3):
+        layer.y_perm.zero_()
+        layer.ffn(-1)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.y_perm, first)
+
+
 def test_act_save_holds_the_preactivations():
     cfg = wl.scaled(wl.CONFIGS["cfg2_mixtral"], name="cfg2_small", T=512, d=128, f=256)
     inp = wl.make_inputs(cfg, DEV)
