@@ -7,9 +7,8 @@
 // up with the logits of ITS token (lane & 31) in registers.  Token fragments are 16-byte global
 // loads; the router weights [d, E] lie the wrong way for a fragment, so 64-k slabs of them
 // are staged in LDS as they are and read with the transposing LDS read (lane layout: see
-// gemm_w8.h).  E <= 64: a block is 32 tokens and its four waves split the k range, so that
-// T / 32 blocks keep every CU busy on what is a pure streaming read of x; larger E: a block
-// is 128 tokens and shares each slab.
+// gemm_w8.h).  A block is 32 tokens; its four waves split the k range (E <= 64) or the experts
+// (larger E), so that T / 32 blocks of four busy waves stream x.
 // Everything else (fp32 layers, other E): each wave owns TB tokens; lane l accumulates the
 // logits of experts l, l+64, ... in fp32 while the token rows stream through LDS, then K
 // rounds of a cross-lane argmax.
@@ -111,11 +110,59 @@ __global__ __launch_bounds__(256) void k_topk(const T* __restrict__ x, const T* 
 }
 
 // ---------------------------------------------------------------------------------------------
-// MFMA path.  NT = 32-expert tiles, KSPLIT = the block's four waves split k (else tokens).
+// MFMA path.  NT = 32-expert tiles.  Up to 64 experts: the block's four waves split k.
 // ---------------------------------------------------------------------------------------------
 typedef short v4i16_t __attribute__((ext_vector_type(4)));
 
-template <int NT, bool KSPLIT>
+// K selection rounds and softmax for the 32 tokens of a wave.  Register q of tile nt holds the
+// logit of expert 32 nt + 8 (q >> 2) + 4 h + (q & 3) of token (lane & 31), h = lane >> 5; the two
+// lanes of a token exchange their best once per round.  s_val: [32][33] floats of the wave.
+template <int NT>
+__device__ inline void select_topk(mfma::f32x16 (&acc)[NT], const float* __restrict__ bias, int E, int K, int t, int Tn,
+                                   float (*s_val)[33], int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    const int lane = threadIdx.x & 63, r = lane & 31, h = lane >> 5;
+    auto expert_of = [&](int nt, int q) { return 32 * nt + 8 * (q >> 2) + 4 * h + (q & 3); };
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = expert_of(nt, q);
+            acc[nt][q] = (e < E) ? acc[nt][q] + (bias != nullptr ? bias[e] : 0.f) : -FLT_MAX;
+        }
+    for (int k = 0; k < K; ++k) {
+        // position p = 16 nt + q counts the lane's values in ascending expert order
+        float bv = -FLT_MAX;
+        int bp = 0;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int q = 0; q < 16; ++q)      // ">" keeps the lowest of equals
+                if (acc[nt][q] > bv) { bv = acc[nt][q]; bp = 16 * nt + q; }
+        int be = 32 * (bp >> 4) + 8 * ((bp & 15) >> 2) + 4 * h + (bp & 3);
+        const float ov = __shfl_xor(bv, 32, 64);
+        const int oe = __shfl_xor(be, 32, 64);
+        const bool partner_wins = ov > bv || (ov == bv && oe < be);
+        if (partner_wins) { bv = ov; be = oe; bp = -1; }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int q = 0; q < 16; ++q)
+                if (16 * nt + q == bp) acc[nt][q] = -FLT_MAX;
+        if (h == 0) {
+            s_val[r][k] = bv;
+            if (t < Tn) topk_idx[(size_t)t * K + k] = be;
+        }
+    }
+    if (h == 0 && t < Tn) {
+        const float top = s_val[r][0];
+        float sum = 0.f;
+        for (int k = 0; k < K; ++k) sum += __expf(s_val[r][k] - top);
+        for (int k = 0; k < K; ++k) topk_w[(size_t)t * K + k] = __expf(s_val[r][k] - top) / sum;
+    }
+}
+
+
+template <int NT>
 __global__ __launch_bounds__(256) void k_topk_mfma(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
                                                    const float* __restrict__ bias, int Tn, int d, int E, int K,
                                                    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
@@ -123,14 +170,13 @@ __global__ __launch_bounds__(256) void k_topk_mfma(const uint16_t* __restrict__ 
     constexpr int EP = NT * 32;                       // padded expert count = slab row length
     constexpr int PITCH = EP * 2;                     // bytes per k-row of a slab
     constexpr int SLAB = 64 * PITCH;                  // 64 k-rows
-    // KSPLIT: one slab per wave, later reused for the reduction ([wave][reg][lane] floats);
-    // else one shared slab.  s_val: the selected logits of each wave's tokens.
-    constexpr int kSlabBytes = KSPLIT ? 4 * (SLAB > NT * 16 * 64 * 4 ? SLAB : NT * 16 * 64 * 4) : SLAB;
+    // one slab per wave, later reused for the reduction ([wave][reg][lane] floats)
+    constexpr int kSlabBytes = 4 * (SLAB > NT * 16 * 64 * 4 ? SLAB : NT * 16 * 64 * 4);
     __shared__ __attribute__((aligned(16))) char s_slab[kSlabBytes];
-    __shared__ float s_val[4][32][33];
+    __shared__ float s_val[32][33];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 31, h = lane >> 5;
-    const int t0 = KSPLIT ? blockIdx.x * 32 : (blockIdx.x * 4 + wave) * 32;
+    const int t0 = blockIdx.x * 32;
     const int tok = min(t0 + r, Tn - 1);
     const uint16_t* xrow = x + (size_t)tok * d + 32 * h;
 
@@ -152,28 +198,36 @@ __global__ __launch_bounds__(256) void k_topk_mfma(const uint16_t* __restrict__ 
     const int chunks_per_row = E / 8;                 // 16-byte pieces of a router-weight row
     const int nsteps = d / 64;
 
-    char* slab = KSPLIT ? s_slab + wave * (kSlabBytes / 4) : s_slab;
-    for (int step = KSPLIT ? wave : 0; step < nsteps; step += KSPLIT ? 4 : 1) {
-        const int k0 = step * 64;
-        // stage w_router[k0 .. k0+63][0 .. E) -> slab[k][e]
-        if constexpr (KSPLIT) {
-            for (int c = lane; c < 64 * chunks_per_row; c += 64) {
-                const int kr = c / chunks_per_row, ce = c - kr * chunks_per_row;
-                *reinterpret_cast<u32x4*>(slab + kr * PITCH + ce * 16) =
-                    *reinterpret_cast<const u32x4*>(w_router + (size_t)(k0 + kr) * E + ce * 8);
-            }
-        } else {
-            __syncthreads();      // everyone has read the previous slab
-            for (int c = threadIdx.x; c < 64 * chunks_per_row; c += 256) {
-                const int kr = c / chunks_per_row, ce = c - kr * chunks_per_row;
-                *reinterpret_cast<u32x4*>(slab + kr * PITCH + ce * 16) =
-                    *reinterpret_cast<const u32x4*>(w_router + (size_t)(k0 + kr) * E + ce * 8);
-            }
-            __syncthreads();
-        }
+    char* slab = s_slab + wave * (kSlabBytes / 4);
+    // Each lane moves up to PITCH / 16 pieces of 16 bytes of a slab; the next step's pieces and
+    // token values are fetched into registers before the current step is computed, so that a
+    // step does not cost a whole memory latency.
+    constexpr int MAXP = PITCH / 16;
+    int w_off[MAXP], s_off[MAXP];
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        const int c = lane + 64 * p, kr = c / max(1, chunks_per_row), ce = c - kr * chunks_per_row;
+        w_off[p] = kr * E + ce * 8;
+        s_off[p] = kr * PITCH + ce * 16;
+    }
+    u32x4 wreg[MAXP];
+    bf16x8 xnext[4];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < MAXP; ++p)
+            if (p < chunks_per_row) wreg[p] = *reinterpret_cast<const u32x4*>(w_router + (size_t)k0 * E + w_off[p]);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) xnext[kk] = *reinterpret_cast<const bf16x8*>(xrow + k0 + 8 * kk);
+    };
+    if (wave < nsteps) fetch(wave * 64);
+    for (int step = wave; step < nsteps; step += 4) {
+#pragma unroll
+        for (int p = 0; p < MAXP; ++p)
+            if (p < chunks_per_row) *reinterpret_cast<u32x4*>(slab + s_off[p]) = wreg[p];
         bf16x8 xf[4];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) xf[kk] = *reinterpret_cast<const bf16x8*>(xrow + k0 + 8 * kk);
+        for (int kk = 0; kk < 4; ++kk) xf[kk] = xnext[kk];
+        if (step + 4 < nsteps) fetch((step + 4) * 64);
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
 #pragma unroll
@@ -187,7 +241,7 @@ __global__ __launch_bounds__(256) void k_topk_mfma(const uint16_t* __restrict__ 
         }
     }
 
-    if constexpr (KSPLIT) {
+    {
         // add the four waves' partial logits in wave order; wave 0 goes on alone
         __syncthreads();
         float* red = reinterpret_cast<float*>(s_slab);
@@ -207,46 +261,98 @@ __global__ __launch_bounds__(256) void k_topk_mfma(const uint16_t* __restrict__ 
                 for (int q = 0; q < 16; ++q) acc[nt][q] += red[((w * NT + nt) * 16 + q) * 64 + lane];
     }
 
-    // register q of tile nt holds expert 32 nt + 8 (q >> 2) + 4 h + (q & 3) of token (lane & 31)
-    auto expert_of = [&](int nt, int q) { return 32 * nt + 8 * (q >> 2) + 4 * h + (q & 3); };
+    select_topk<NT>(acc, bias, E, K, t0 + r, Tn, s_val, topk_idx, topk_w);
+}
+
+// More than 64 experts: a block is 32 tokens and its four waves split the EXPERTS (NT / 4 tiles
+// each, every wave over the whole k range with its own slab of its experts' columns), so that
+// T / 32 blocks of four busy waves exist even when T is a few thousand.  The logits then meet in
+// LDS and wave 0 selects.
+template <int NT>
+__global__ __launch_bounds__(256) void k_topk_mfma_esplit(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
+                                                          const float* __restrict__ bias, int Tn, int d, int E, int K,
+                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    using namespace mfma;
+    constexpr int NTW = NT / 4;                       // expert tiles per wave
+    constexpr int EPW = NTW * 32, PITCH = EPW * 2, SLAB = 64 * PITCH;
+    constexpr int kLogitBytes = 32 * (NT * 32 + 1) * 4;                   // [32 tokens][experts + 1] floats
+    constexpr int kBytes = 4 * SLAB > kLogitBytes ? 4 * SLAB : kLogitBytes;
+    __shared__ __attribute__((aligned(16))) char s_mem[kBytes];
+    __shared__ float s_val[32][33];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = lane & 31, h = lane >> 5;
+    const int t0 = blockIdx.x * 32;
+    const int tok = min(t0 + r, Tn - 1);
+    const uint16_t* xrow = x + (size_t)tok * d + 32 * h;
+    const int e0 = wave * EPW;                        // this wave's first expert
+
+    for (int i = threadIdx.x * 16; i < 4 * SLAB; i += 256 * 16) *reinterpret_cast<u32x4*>(s_mem + i) = u32x4{0, 0, 0, 0};
+    __syncthreads();
+
+    f32x16 acc[NTW];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[nt][q] = 0.f;
+    const int g = lane >> 4, i4 = lane & 15;
+    const int tr_off = (32 * (g >> 1) + (i4 >> 2)) * PITCH + (16 * (g & 1) + 4 * (i4 & 3)) * 2;
+    const int chunks = max(0, min(EPW, E - e0)) / 8;  // 16-byte pieces of this wave's part of a router-weight row
+    char* slab = s_mem + wave * SLAB;
+    // as above: the next step's pieces and token values travel while this step is computed
+    constexpr int MAXP = PITCH / 16;
+    int w_off[MAXP], s_off[MAXP];
+#pragma unroll
+    for (int p = 0; p < MAXP; ++p) {
+        const int c = lane + 64 * p, kr = c / max(1, chunks), ce = c - kr * chunks;
+        w_off[p] = kr * E + e0 + ce * 8;
+        s_off[p] = kr * PITCH + ce * 16;
+    }
+    u32x4 wreg[MAXP];
+    bf16x8 xnext[4];
+    auto fetch = [&](int k0) {
+#pragma unroll
+        for (int p = 0; p < MAXP; ++p)
+            if (p < chunks) wreg[p] = *reinterpret_cast<const u32x4*>(w_router + (size_t)k0 * E + w_off[p]);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) xnext[kk] = *reinterpret_cast<const bf16x8*>(xrow + k0 + 8 * kk);
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < d; k0 += 64) {
+#pragma unroll
+        for (int p = 0; p < MAXP; ++p)
+            if (p < chunks) *reinterpret_cast<u32x4*>(slab + s_off[p]) = wreg[p];
+        bf16x8 xf[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) xf[kk] = xnext[kk];
+        if (k0 + 64 < d) fetch(k0 + 64);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                const char* p = slab + tr_off + (8 * kk) * PITCH + nt * 64;
+                const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)(p));
+                const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)(p + 4 * PITCH));
+                const bf16x8 wf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[kk], acc[nt], 0, 0, 0);
+            }
+        }
+    }
+    // logits -> LDS [token][expert] (row length odd in floats: the 32 tokens of a wave write different banks)
+    __syncthreads();
+    float* logit = reinterpret_cast<float*>(s_mem);
+    constexpr int LP = NT * 32 + 1;
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) logit[r * LP + e0 + 32 * nt + 8 * (q >> 2) + 4 * h + (q & 3)] = acc[nt][q];
+    __syncthreads();
+    if (wave != 0) return;
+    f32x16 all[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int e = expert_of(nt, q);
-            acc[nt][q] = (e < E) ? acc[nt][q] + (bias != nullptr ? bias[e] : 0.f) : -FLT_MAX;
-        }
-    const int t = t0 + r;
-    for (int k = 0; k < K; ++k) {
-        // position p = 16 nt + q counts the lane's values in ascending expert order
-        float bv = -FLT_MAX;
-        int bp = 0;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int q = 0; q < 16; ++q)      // ">" keeps the lowest of equals
-                if (acc[nt][q] > bv) { bv = acc[nt][q]; bp = 16 * nt + q; }
-        int be = 32 * (bp >> 4) + 8 * ((bp & 15) >> 2) + 4 * h + (bp & 3);
-        const float ov = __shfl_xor(bv, 32, 64);
-        const int oe = __shfl_xor(be, 32, 64);
-        const bool partner_wins = ov > bv || (ov == bv && oe < be);
-        if (partner_wins) { bv = ov; be = oe; bp = -1; }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int q = 0; q < 16; ++q)
-                if (16 * nt + q == bp) acc[nt][q] = -FLT_MAX;
-        if (h == 0) {
-            s_val[wave][r][k] = bv;
-            if (t < Tn) topk_idx[(size_t)t * K + k] = be;
-        }
-    }
-    if (h == 0 && t < Tn) {
-        const float top = s_val[wave][r][0];
-        float sum = 0.f;
-        for (int k = 0; k < K; ++k) sum += __expf(s_val[wave][r][k] - top);
-        for (int k = 0; k < K; ++k) topk_w[(size_t)t * K + k] = __expf(s_val[wave][r][k] - top) / sum;
-    }
+        for (int q = 0; q < 16; ++q) all[nt][q] = logit[r * LP + 32 * nt + 8 * (q >> 2) + 4 * h + (q & 3)];
+    select_topk<NT>(all, bias, E, K, t0 + r, Tn, s_val, topk_idx, topk_w);
 }
 
 template <typename T>
@@ -273,13 +379,13 @@ int launch_topk(const fine_shape& s, const void* x, const void* w_router, const 
     if (s.T == 0) return FINE_OK;
     if (s.dtype == FINE_F32) return dispatch<float>(s, x, w_router, bias, topk_idx, topk_w, st);
     if (s.E % 8 == 0 && s.E <= 256 && s.d % 64 == 0) {
-#define FINE_TOPK_MFMA(NT, KSPLIT, GRID)                                                                        \
-    hipLaunchKernelGGL((k_topk_mfma<NT, KSPLIT>), dim3(GRID), dim3(256), 0, st, (const uint16_t*)x,             \
+#define FINE_TOPK_MFMA(KERNEL)                                                                                  \
+    hipLaunchKernelGGL((KERNEL), dim3(cdiv(s.T, 32)), dim3(256), 0, st, (const uint16_t*)x,                     \
                        (const uint16_t*)w_router, bias, s.T, s.d, s.E, s.K, topk_idx, topk_w)
-        if (s.E <= 32) FINE_TOPK_MFMA(1, true, cdiv(s.T, 32));
-        else if (s.E <= 64) FINE_TOPK_MFMA(2, true, cdiv(s.T, 32));
-        else if (s.E <= 128) FINE_TOPK_MFMA(4, false, cdiv(s.T, 128));
-        else FINE_TOPK_MFMA(8, false, cdiv(s.T, 128));
+        if (s.E <= 32) FINE_TOPK_MFMA(k_topk_mfma<1>);
+        else if (s.E <= 64) FINE_TOPK_MFMA(k_topk_mfma<2>);
+        else if (s.E <= 128) FINE_TOPK_MFMA(k_topk_mfma_esplit<4>);
+        else FINE_TOPK_MFMA(k_topk_mfma_esplit<8>);
 #undef FINE_TOPK_MFMA
         FINE_LAUNCH_CHECK();
         return FINE_OK;
