@@ -249,7 +249,7 @@ def run_cpu_baseline(cfg, inp, topk_idx, topk_w):
     sched.schedule(idx, cfg.E, cfg.G)
     t_sched = time.perf_counter() - t0
     per_token = 6.0 * cfg.K * cfg.d * cfg.f
-    n = int(min(cfg.T, max(16, 1.5e12 // per_token)))
+    n = int(min(cfg.T, max(16, 5e12 // per_token)))
     tokens = np.arange(n)
     x64 = inp.x[:n].double().cpu().numpy()
     x_full = np.zeros((cfg.T, cfg.d))
