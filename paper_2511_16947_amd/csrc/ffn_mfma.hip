@@ -129,23 +129,28 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     __shared__ int s_last;
     const int nblk = gridDim.x, bid = xcd_contiguous_id();
     // the cut pays when the k-steps it saves (the last round would take nk, the cut takes
-    // rest * nk / nblk) outweigh writing, re-reading and adding up partial tiles; measured on three
-    // workloads, the break-even is about 16 WM steps (GEMM 2 of a rank with 128 tiles and 224 steps
-    // gains a lot, half a round of 64-step tiles gains nothing, short k-loops lose)
+    // rest * nk / nblk) outweigh writing, re-reading and adding up partial tiles.  Measured
+    // break-even: about 16 steps on the 256-row tile (GEMM 2 of a rank with 128 tiles of 224 steps
+    // gains 30 %, half a round of 64-step GEMM 1 tiles a little); on the 128-row tile, whose
+    // workloads stream weights from HBM, the cut only pays for long k ranges (32 steps).
     const int whole_rounds = (total / nblk) * nblk;
-    const bool cut = W8 && (long long)nk * (nblk - (total - whole_rounds)) > (long long)16 * WM * nblk;
+    const bool cut = W8 && (long long)nk * (nblk - (total - whole_rounds)) > (long long)(WM == 4 ? 16 : 32) * nblk;
     const int full = cut ? whole_rounds : total;
     const int rest = total - full;
     const int per = (rest * nk + nblk - 1) / nblk;
     int32_t* counters = count + kSkCounterOffset;
     auto slot_of = [&](int blk, int t) { return blk * 2 + (((blk * per) / nk) == t ? 0 : 1); };
-    // Partial sums travel as 8-byte agent-scope atomic stores and loads: they are written
-    // through and read past the per-XCD L2 one by one, so no cache-wide write-back or
-    // invalidate (a fence) is needed, which would cost every block on the XCD its cached
-    // operand tiles.
-    auto slot_ptr = [&](int slot, int j) {
-        return reinterpret_cast<uint64_t*>(sk_partials) + ((size_t)slot * (WM * WN * 8) + j) * (WAVES_M * WAVES_N * 64) + threadIdx.x;
-    };
+    // Partial sums travel as 16-byte buffer stores and loads with the sc0 sc1 cache policy: they
+    // are written through and read past the per-XCD L2 one by one, so no cache-wide write-back or
+    // invalidate (a fence) is needed, which would cost every block on the XCD its cached operand
+    // tiles.  A slot is [WM*WN*4 groups][threads] x 16 bytes; group g of a thread = registers
+    // 4 (g & 3) .. + 3 of accumulator tile g >> 2.  Two accumulator tiles' worth of loads (8 x 16
+    // bytes per lane) are in flight at a time.
+    constexpr int kThreadsBlk = WAVES_M * WAVES_N * 64;
+    constexpr int kSlotBytes = WM * WN * 4 * kThreadsBlk * 16;
+    constexpr int kCoherent = 1 | 16;      // sc0 | sc1
+    const __amdgpu_buffer_rsrc_t sk_rs =
+        __builtin_amdgcn_make_buffer_rsrc((void*)sk_partials, 0, (int)(2 * 256 * (size_t)kSlotBytes), 0x00020000);
 #ifdef FINE_PROFILE_LOOP
     const unsigned long long blk_w0 = wall_clock64(), blk_c0 = clock64();
     int blk_tiles = 0;
@@ -177,15 +182,14 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                 const int t = work - full;
                 const int first = (t * nk) / per, last = (t * nk + nk - 1) / per;
                 const int mine = slot_of(bid, t);
-                uint64_t* wp = slot_ptr(mine, 0);
                 static_for<WM * WN>([&](auto m) {
-                    static_for<8>([&](auto q) {
+                    static_for<4>([&](auto q) {
                         const f32x16& v = acc[m.value / WN][m.value % WN];
-                        const float2 pr = make_float2(v[2 * q.value], v[2 * q.value + 1]);
-                        __hip_atomic_store(wp, __builtin_bit_cast(uint64_t, pr), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        wp += WAVES_M * WAVES_N * 64;
+                        const f32x4 part = {v[4 * q.value], v[4 * q.value + 1], v[4 * q.value + 2], v[4 * q.value + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, part), sk_rs, threadIdx.x * 16,
+                                                               mine * kSlotBytes + (m.value * 4 + q.value) * kThreadsBlk * 16,
+                                                               kCoherent);
                     });
-                    __builtin_amdgcn_sched_barrier(0);      // one group's addresses at a time
                 });
                 __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0): this thread's partial sums have been written
                 __syncthreads();
@@ -197,18 +201,18 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                 if (finish) {
                     zero_acc<WM, WN>(acc);
                     for (int blk = first; blk <= last; ++blk) {
-                        const uint64_t* rp = slot_ptr(slot_of(blk, t), 0);
-                        static_for<WM * WN>([&](auto m) {
-                            uint64_t v[8];
-                            static_for<8>([&](auto q) {
-                                v[q.value] = __hip_atomic_load(rp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                rp += WAVES_M * WAVES_N * 64;
+                        const int sl = slot_of(blk, t);
+                        static_for<WM * WN / 2>([&](auto mp) {
+                            u32x4 v[8];
+                            static_for<8>([&](auto g) {
+                                v[g.value] = __builtin_amdgcn_raw_buffer_load_b128(
+                                    sk_rs, threadIdx.x * 16, sl * kSlotBytes + (mp.value * 8 + g.value) * kThreadsBlk * 16, kCoherent);
                             });
-                            f32x16& a = acc[m.value / WN][m.value % WN];
-                            static_for<8>([&](auto q) {
-                                const float2 pr = __builtin_bit_cast(float2, v[q.value]);
-                                a[2 * q.value] += pr.x;
-                                a[2 * q.value + 1] += pr.y;
+                            static_for<8>([&](auto g) {
+                                constexpr int m = mp.value * 2 + g.value / 4, q = g.value % 4;
+                                const f32x4 part = __builtin_bit_cast(f32x4, v[g.value]);
+                                f32x16& a = acc[m / WN][m % WN];
+                                a[4 * q] += part[0]; a[4 * q + 1] += part[1]; a[4 * q + 2] += part[2]; a[4 * q + 3] += part[3];
                             });
                             __builtin_amdgcn_sched_barrier(0);      // keeps the loads from piling up in registers
                         });
