@@ -38,6 +38,9 @@ def parse():
                     help="per_rank: one fine_grouped_ffn call per logical rank (default); fused: one call for all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true")
+    ap.add_argument("--recompute", action="store_true",
+                    help="with backward: do not keep the pre-activations of the forward pass; the backward pass "
+                         "recomputes them with another GEMM 1 (default: the forward pass saves them)")
     ap.add_argument("--detail-iters", type=int, default=10)
     ap.add_argument("--also-fused", action="store_true", help="also time one fine_grouped_ffn call for all ranks")
     ap.add_argument("--tile", type=int, default=0, choices=[0, 1, 2, 3],
@@ -95,6 +98,8 @@ def main():
         d_wg = torch.empty(s.E, s.d, s.f, dtype=torch.float32, device=dev)
         d_wu = torch.empty(s.E, s.d, s.f, dtype=torch.float32, device=dev)
         d_wd = torch.empty(s.E, s.f, s.d, dtype=torch.float32, device=dev)
+    # training keeps the pre-activations A|B [P,2f] of the forward pass for the backward pass
+    act_save = torch.empty(s.P, 2 * s.f, dtype=s.torch_dtype, device=dev) if do_bwd and not args.recompute else None
 
     def st_topk():
         fm.fine_topk(s, inp.x, inp.w_router, inp.bias, topk_idx, topk_w)
@@ -106,7 +111,7 @@ def main():
         fm.fine_permute(s, inp.x, sb.pair_of_row, x_perm)
 
     def st_ffn_rank(r, shp=s):
-        fm.fine_grouped_ffn(shp, r, x_perm, inp.w_gate, inp.w_up, inp.w_down, sb.seg_off, y_perm, None, ws_ffn)
+        fm.fine_grouped_ffn(shp, r, x_perm, inp.w_gate, inp.w_up, inp.w_down, sb.seg_off, y_perm, act_save, ws_ffn)
 
     def st_ffn():
         if args.ffn == "fused":
@@ -119,7 +124,7 @@ def main():
         fm.fine_combine(s, y_perm, sb.row_of_pair, topk_w, out)
 
     def st_backward():
-        fm.fine_backward(s, -1, inp.d_out, x_perm, y_perm, None, inp.w_gate, inp.w_up, inp.w_down, sb.row_of_pair,
+        fm.fine_backward(s, -1, inp.d_out, x_perm, y_perm, act_save, inp.w_gate, inp.w_up, inp.w_down, sb.row_of_pair,
                          sb.pair_of_row, sb.seg_off, topk_w, d_x, d_topk_w, d_wg, d_wu, d_wd, False, ws_bwd)
 
     stages = [("topk", st_topk), ("sched", st_sched), ("permute", st_permute), ("ffn", st_ffn), ("combine", st_combine)]
@@ -227,7 +232,8 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": s.T, "d": s.d, "f": s.f, "E": s.E, "K": s.K, "G": s.G,
-                   "placement": "every expert on every rank", "ffn_calls": args.ffn, "backward": bool(do_bwd)},
+                   "placement": "every expert on every rank", "ffn_calls": args.ffn, "backward": bool(do_bwd),
+                   "pre_activations": (None if not do_bwd else "recomputed" if args.recompute else "saved by the forward pass")},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "detail": detail,
     }
     print(json.dumps(line))
