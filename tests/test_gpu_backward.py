@@ -38,6 +38,9 @@ def small_train_cfgs():
         wl.scaled(c5, name="cfg5_small", T=2048, d=128, f=256),
         wl.scaled(c5, name="cfg5_ragged", T=1024, d=192, f=320, E=16, K=2, G=4, bias_kind="scaled_z", bias_scale=1.5),
         wl.scaled(c5, name="cfg5_topk4", T=512, d=256, f=128, E=32, K=4, G=8, bias_kind="scaled_z", bias_scale=2.0),
+        # one long segment per expert (K = 1, two experts, one rank): whole 256-row tiles and a ragged
+        # tail in the data-gradient kernels, a long contraction in the weight gradients
+        wl.scaled(c5, name="cfg5_long", T=1200, d=128, f=192, E=8, K=1, G=1, bias_kind="one_hot", bias_scale=3.0),
     ]
 
 

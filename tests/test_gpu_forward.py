@@ -98,6 +98,11 @@ def small_cfgs():
         wl.scaled(c["cfg4_dsv3"], name="cfg4_small", T=512, d=192, f=128),
         wl.scaled(c["cfg5_train"], name="cfg5_small", T=2048, d=128, f=256),
         wl.scaled(c["cfg1_tiny_f32"], name="f32_odd", T=60, d=50, f=70, E=5, K=3, G=3),  # nothing a multiple of a tile
+        # bf16 with every edge at once: d narrower than a column tile, f = 2.5 column tiles, ragged
+        # segments on 3 ranks, E not a multiple of 8 (lane-per-expert gate)
+        wl.LayerConfig("bf16_odd", 201, 192, 320, 3, 2, 3, "bf16", 9, "scaled_z", 1.0),
+        # one expert, one rank, one token tile: a single segment of 96 rows
+        wl.LayerConfig("bf16_single", 96, 64, 64, 8, 1, 1, "bf16", 10, "one_hot", 50.0),
     ]
 
 
