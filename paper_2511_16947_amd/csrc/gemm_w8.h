@@ -394,13 +394,11 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[WM][2], OA& oa,
         return last_tile;
     };
 
-    // prologue: ring stages 0 .. RING-2, tile 0 into LDS, tile 1 into the other buffer (row
-    // DMA) or into registers; everything lands before the first barrier, so the counts in the
-    // loop only ever concern the loop's own requests
+    // prologue: ring stages 0 .. RING-2, tile 0 into LDS, tile 1 into the other buffer (row DMA)
     const KTile t0 = next_tile();
     KTile n1 = next_tile();
     {
-        static_for<RING - 1>([&](auto st) {          // stage st: half (st & 1) of tile st / 2
+        auto ring_stage = [&](auto st) {             // stage st: half (st & 1) of tile st / 2
             const KTile& t = st.value < 2 ? t0 : n1;
             constexpr int half = (st.value & 1) * 32;
             if constexpr (kA == kRing) {
@@ -411,16 +409,19 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[WM][2], OA& oa,
                 ob.template issue<0>(t.b + half, t.base, t.end, b_at(0, st.value));
                 ob.template issue<1>(t.b + half, t.base, t.end, b_at(0, st.value));
             }
-        });
-        if constexpr (kA == kRow) {
-            static_for<OA::kInstr>([&](auto j) { oa.template row_issue<j.value>(t0.a, 0, a_at(0, 0)); });
-            static_for<OA::kInstr>([&](auto j) { oa.template row_issue<j.value>(n1.a, 0, a_at(1, 0)); });
-        }
-        if constexpr (kB == kRow) {
-            static_for<OB::kInstr>([&](auto j) { ob.template row_issue<j.value>(t0.b, t0.sel, b_at(0, 0)); });
-            static_for<OB::kInstr>([&](auto j) { ob.template row_issue<j.value>(n1.b, n1.sel, b_at(1, 0)); });
-        }
-        wait_vm_lgkm<0>();
+        };
+        // first what the first half step computes on ...
+        ring_stage(IntC<0>{});
+        if constexpr (kA == kRow) static_for<OA::kInstr>([&](auto j) { oa.template row_issue<j.value>(t0.a, 0, a_at(0, 0)); });
+        if constexpr (kB == kRow) static_for<OB::kInstr>([&](auto j) { ob.template row_issue<j.value>(t0.b, t0.sel, b_at(0, 0)); });
+        // ... then the rest, in the order the loop needs it; the loop's counts hold from its first
+        // barrier on because nothing here is younger than what they allow to be outstanding
+        static_for<RING - 2>([&](auto st) { ring_stage(IntC<st.value + 1>{}); });
+        if constexpr (kA == kRow) static_for<OA::kInstr>([&](auto j) { oa.template row_issue<j.value>(n1.a, 0, a_at(1, 0)); });
+        if constexpr (kB == kRow) static_for<OB::kInstr>([&](auto j) { ob.template row_issue<j.value>(n1.b, n1.sel, b_at(1, 0)); });
+        constexpr int kLater = (RING - 2) * 2 * ((kA == kRing ? 1 : 0) + (kB == kRing ? 1 : 0)) +
+                               (kA == kRow ? OA::kInstr : 0) + (kB == kRow ? OB::kInstr : 0);
+        wait_vm_lgkm<kLater>();
         block_barrier();
     }
     Frags<WM> f0, f1;
