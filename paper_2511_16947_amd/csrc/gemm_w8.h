@@ -279,9 +279,11 @@ struct Frags {
 //   a_next / b_next   where the next half step's first fragments are (read after the barrier)
 //   a_dst / b_dst     what is filled meanwhile: the other LDS buffer / the free ring stage
 //   ka, kb            where the data to fetch starts (see KTile)
+//   ISSUE             false for the last half steps of a tile, which have nothing left to request:
+//                     no side operations, and the barrier waits for everything outstanding
 //   nf                (RAGGED_M only) how many of the wave's four 32-row fragments hold valid rows:
 //                     MFMAs and fragment reads of the others are skipped
-template <int P, bool BARRIER, bool RAGGED_M, int RING, int WM, typename OA, typename OB>
+template <int P, bool BARRIER, bool RAGGED_M, int RING, bool ISSUE, int WM, typename OA, typename OB>
 __device__ inline void half_step8(const char* a_src, const char* b_src, const char* a_next, const char* b_next,
                                   char* a_dst, char* b_dst, f32x16 (&acc)[WM][2], Frags<WM>& f0, Frags<WM>& f1, OA& oa,
                                   OB& ob, ptrdiff_t ka, ptrdiff_t kb, int kbase, int kend, int ksel, int nf, int prof_kt = 0) {
@@ -292,7 +294,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
     constexpr int KA0 = ringA ? 0 : (2 * P + 2) & 3, KB0 = ringB ? 0 : (2 * P + 2) & 3;     // next first
     auto side = [&](auto slot_c) {
 #ifndef FINE_DBG_NOSIDE
-        static_for<2>([&](auto which) {
+        if constexpr (ISSUE) static_for<2>([&](auto which) {
             constexpr SideOp o = S::op[P][slot_c.value][which.value];
 #ifdef FINE_DBG_NODMA
             if constexpr (is_dma(o)) return;
@@ -345,7 +347,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
     if (blockIdx.x == 0 && threadIdx.x == 0 && prof_kt < 64) g_prof[prof_kt * 8 + 1 + 4 * P] = clock64();
 #endif
     if constexpr (BARRIER) {
-        wait_vm_lgkm<vm_allowed<S, RING>(P)>();
+        wait_vm_lgkm<(ISSUE ? vm_allowed<S, RING>(P) : 0)>();
         block_barrier();
     }
 #ifdef FINE_PROFILE_LOOP
@@ -367,9 +369,9 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
 // Half step h computes on ring stage h / on the LDS buffer of its tile.  Its barrier sits
 // between its two sub-steps, after the last fragment read of stage h: from there on stage h's
 // slot is free, and stage h + 1 (requested two half steps earlier) has landed for everyone.
-// During half step h the DMA fills the slot of stage h + 3 (free since the barrier of h - 1)
-// and the registers write tile kt + 1 to the other LDS buffer and reload with tile kt + 2.
-// Fetches past the last tile repeat it; nobody reads them.
+// During half step h the ring DMA fills the slot of stage h + 3 (free since the barrier of h - 1);
+// a row operand's buffer of tile kt is refilled with tile kt + 2 after the barrier of that tile's
+// second half step.
 // RAGGED_M: the wave computes only its first nf 32-row fragments (a row tile at the end of a
 // segment); the tile is still loaded whole.
 // RING: stages of a ring operand's ring (4 or 5; operand A's ring always has 4).
@@ -430,27 +432,37 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[WM][2], OA& oa,
         f0.a[i.value] = oa.template frag<0, i.value>(a_at(0, 0));
     });
     if (!(RAGGED_M && nf == 0)) static_for<2>([&](auto i) { f0.b[i.value] = ob.template frag<0, i.value>(b_at(0, 0)); });
-    for (int kt = 0; kt < nk; ++kt) {
-        const KTile n2 = next_tile();          // tile kt + 2 (n1 = tile kt + 1)
+    // Half step 0 of tile kt requests (ring) the second half of tile kt + 1, half step 1 (ring) the
+    // first half of tile kt + 2 and (row) tile kt + 2.  Past the last tile there is nothing to
+    // request: the last two tiles run as straight-line code after the loop without those requests.
+    KTile n2 = n1;
+    auto iteration = [&](int kt, auto issue0, auto issue1) {
         const int h = 2 * kt;
         FINE_PROF(0);
-        // A ring operand's DMA in half step h requests stage h + RING - 1, i.e. tile
-        // kt + (P + RING - 1) / 2, half (P + RING - 1) % 2.  A row DMA (second half step, after its barrier) refills the
-        // buffer of tile kt, just read for the last time, with tile kt + 2.
         const KTile& d0 = (RING == 4) ? n1 : n2;      // ring, P = 0
         constexpr int d0_half = (RING == 4) ? 32 : 0, d1_half = (RING == 4) ? 0 : 32;
-        half_step8<0, kAnyRing, RAGGED_M, RING, WM>(
+        half_step8<0, kAnyRing, RAGGED_M, RING, issue0.value, WM>(
             a_at(kt, h), b_at(kt, h), a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + RING - 1),
             b_at(kt + 1, h + RING - 1), acc, f0, f1, oa, ob, kA == kRing ? d0.a + d0_half : n2.a,
             kB == kRing ? d0.b + d0_half : n2.b, d0.base, d0.end, 0, nf, kt);
         FINE_PROF(3);
-        half_step8<1, true, RAGGED_M, RING, WM>(
+        half_step8<1, true, RAGGED_M, RING, issue1.value, WM>(
             a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + 2), b_at(kt + 1, h + 2),
             kA == kRow ? a_at(kt, 0) : a_at(kt + 1, h + RING), kB == kRow ? b_at(kt, 0) : b_at(kt + 1, h + RING), acc, f0,
             f1, oa, ob, kA == kRing ? n2.a + d1_half : n2.a, kB == kRing ? n2.b + d1_half : n2.b, n2.base, n2.end, n2.sel, nf, kt);
         FINE_PROF(7);
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) {
+        n2 = next_tile();                      // tile kt + 2 (n1 = tile kt + 1)
+        iteration(kt, std::true_type{}, std::true_type{});
         n1 = n2;
     }
+    if (kt + 1 < nk) {                         // second to last tile: the last tile's second half is still to come
+        iteration(kt, std::true_type{}, std::false_type{});
+        ++kt;
+    }
+    iteration(kt, std::false_type{}, std::false_type{});
     wait_vm_lgkm<0>();
     block_barrier();
 }
