@@ -1,0 +1,158 @@
+"""Pins for oracle/placement.py (CPU only).
+
+Each test checks the oracle against something other than itself: exhaustive
+search over replica-count vectors and over candidates, an LP solved by HiGHS,
+the defining properties of a placement, and the outcome of the Section 6.3
+experiment for placements built from known loads.
+"""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+from scipy.optimize import linprog
+
+import workloads as wl
+from oracle import placement, sched
+
+
+# ------------------------------------------------------------------ generator
+
+def unmix32(h):
+    """Inverse of the finaliser, written from its definition: undo each
+    xor-shift by repeated substitution and each multiplication by the
+    multiplier's inverse modulo 2^32."""
+    def unshift(v, s):
+        out = v
+        for _ in range(32 // s + 1):
+            out = v ^ (out >> s)
+        return out
+    inv1 = pow(0x85EBCA6B, -1, 1 << 32)
+    inv2 = pow(0xC2B2AE35, -1, 1 << 32)
+    h = unshift(h, 16)
+    h = (h * inv2) & 0xFFFFFFFF
+    h = unshift(h, 13)
+    h = (h * inv1) & 0xFFFFFFFF
+    return unshift(h, 16)
+
+
+def test_mix32_is_a_bijection_that_mixes():
+    rng = np.random.default_rng(0)
+    vals = [0, 1, 0xFFFFFFFF] + [int(v) for v in rng.integers(0, 1 << 32, 200)]
+    assert placement.mix32(0) == 0
+    for v in vals:
+        assert unmix32(placement.mix32(v)) == v
+    # flipping one input bit flips about half of the output bits
+    flips = [bin(placement.mix32(v) ^ placement.mix32(v ^ (1 << b))).count("1") for v in vals[3:53] for b in range(32)]
+    assert 14 < np.mean(flips) < 18
+
+
+def test_rank_keys_differ_between_candidates_experts_and_ranks():
+    keys = {placement.rank_key(7, c, e, g) for c in range(8) for e in range(16) for g in range(16)}
+    assert len(keys) >= 8 * 16 * 16 - 1          # 2048 draws from 2^32: a collision is a 1 in 2000 event
+    assert placement.rank_key(7, 0, 1, 2) != placement.rank_key(8, 0, 1, 2)
+
+
+# ------------------------------------------------------------------ replica counts
+
+def test_greedy_counts_minimise_the_largest_load_per_replica():
+    """The greedy rule is the classical one for min-max apportionment: no count
+    vector with the same total has a smaller largest load per replica."""
+    rng = np.random.default_rng(1)
+    for trial in range(40):
+        E, G = int(rng.integers(2, 5)), int(rng.integers(2, 5))
+        slots = int(rng.integers((E + G - 1) // G, E + 1))
+        load = rng.integers(0, 50, E)
+        counts = placement.replica_counts(load, G, slots)
+        total = min(G * slots, E * G)
+        assert counts.sum() == total and counts.min() >= 1 and counts.max() <= G
+        worst = max(Fraction(int(l), int(c)) for l, c in zip(load, counts))
+        best = min(max(Fraction(int(l), c) for l, c in zip(load, cv))
+                   for cv in itertools.product(range(1, G + 1), repeat=E) if sum(cv) == total)
+        assert worst == best, (load, counts)
+
+
+def test_counts_special_cases():
+    assert list(placement.replica_counts([5, 5, 5, 5], 4, 2)) == [2, 2, 2, 2]
+    assert list(placement.replica_counts([8, 1, 1], 4, 2)) == [4, 2, 2]      # capped at G, the rest moves on
+    assert list(placement.replica_counts([0, 0, 0], 2, 3)) == [2, 2, 2]      # no load: ties go to the lower index
+    assert list(placement.replica_counts([6, 3], 4, 1)) == [3, 1]            # 6/1 > 3/1, 6/2 = 3/1 -> lower index
+    with pytest.raises(ValueError):
+        placement.replica_counts([1, 1, 1], 2, 1)
+
+
+# ------------------------------------------------------------------ candidates
+
+def test_drawn_placements_are_valid_and_differ():
+    rng = np.random.default_rng(2)
+    for trial in range(20):
+        G = int(rng.choice([2, 4, 8, 16]))
+        E = int(rng.integers(1, 4 * G + 1))
+        slots = int(rng.integers((E + G - 1) // G, (E + G - 1) // G + 4))
+        load = rng.integers(0, 1000, E)
+        counts = placement.replica_counts(load, G, slots)
+        seen = set()
+        for c in range(6):
+            place = placement.draw_placement(counts, G, slots, 11, c)
+            assert (place.sum(axis=1) == counts).all()
+            assert place.sum(axis=0).max() <= slots
+            if counts.sum() == G * slots:
+                assert (place.sum(axis=0) == slots).all()
+            assert np.array_equal(place, placement.draw_placement(counts, G, slots, 11, c))
+            seen.add(place.tobytes())
+        if G >= 8 and E >= 4 and counts.max() < G:
+            assert len(seen) > 1
+
+
+def test_draw_follows_the_keys():
+    """The first expert drawn sees equal free slots everywhere, so it takes
+    exactly the ranks with the largest keys."""
+    counts = np.array([1, 3, 2, 2])
+    place = placement.draw_placement(counts, 8, 1, 5, 3)
+    keys = [placement.rank_key(5, 3, 1, g) for g in range(8)]
+    assert set(np.nonzero(place[1])[0]) == set(np.argsort(keys)[-3:])
+
+
+# ------------------------------------------------------------------ search
+
+def highs_optimum(load, place):
+    E, G = place.shape
+    var = [(e, g) for e in range(E) for g in range(G) if place[e, g]]
+    n = len(var) + 1
+    c = np.zeros(n); c[-1] = 1.0
+    A_eq = np.zeros((E, n)); A_ub = np.zeros((G, n))
+    for j, (e, g) in enumerate(var):
+        A_eq[e, j] = 1.0
+        A_ub[g, j] = 1.0
+    A_ub[:, -1] = -1.0
+    res = linprog(c, A_ub=A_ub, b_ub=np.zeros(G), A_eq=A_eq, b_eq=np.asarray(load, dtype=float),
+                  bounds=[(0, None)] * n, method="highs")
+    assert res.status == 0
+    return res.fun
+
+
+def test_search_returns_the_best_candidate_and_its_lp_optimum():
+    load = wl.zipf_loads(16, 4096, 1.2, 0)
+    counts, scores, best, place = placement.search(load, 8, 4, 24, 3)
+    assert len(scores) == 24
+    # recompute every candidate's score from the LP itself (Eq. 1 through HiGHS)
+    lp = [highs_optimum(load, placement.draw_placement(counts, 8, 4, 3, c)) for c in range(24)]
+    for c in range(24):
+        assert abs(float(scores[c]) - lp[c]) < 1e-6 * lp[c]
+    assert scores[best] == min(scores) and best == scores.index(min(scores))
+    assert np.array_equal(place, placement.draw_placement(counts, 8, 4, 3, best))
+    assert scores[best] >= Fraction(4096, 8)
+
+
+def test_zipf_experiment_asymmetric_placement_balances_completely():
+    """Section 6.3 (DP = 8, 32 experts, as many replica slots as the symmetric
+    placement has): where uniform replica counts stop balancing (s > 1), a
+    placement built from the loads balances completely."""
+    P, G, E, slots = 8 * 4096, 8, 32, 8
+    symmetric = wl.placement_complete_plus_matching(8)
+    for s in (1.3, 1.6, 2.0):
+        load = wl.zipf_loads(E, P, s, 0)
+        assert sched.min_max_load(load, symmetric) > P // G
+        counts, scores, best, place = placement.search(load, G, slots, 32, 0)
+        assert scores[best] == Fraction(P, G), (s, scores[best])
+        assert sched.min_max_load(load, place) == P // G
