@@ -169,6 +169,47 @@ int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
                   void* d_x, float* d_topk_w, float* d_w_gate, float* d_w_up, float* d_w_down,
                   int accumulate, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Expert placement from known expert loads (Section 5.3), scored by Eq. 3 (Section 5.1).
+ * Only E and G of `shape` matter.  A rank holds at most `slots` replicas and the replicas of
+ * an expert sit on distinct ranks (G * slots >= E, else FINE_INVALID_ARG).
+ *
+ * fine_replica_counts: the greedy rule of Section 5.3, step 1.  Every expert starts with one
+ * replica; each of the remaining G * slots - E replicas goes to the expert with the largest
+ * load per replica among those with fewer than G (compared exactly; ties to the lower expert
+ * index); replicas nobody can take stay unused.   load [E] int32 (negative reads as 0) ->
+ * counts [E] int32 out.
+ */
+int fine_replica_counts(const fine_shape* shape, const int32_t* load, int32_t slots, int32_t* counts,
+                        void* stream);
+
+/*
+ * Eq. 3 for n given placements: m = max over non-empty rank subsets S of
+ * (sum of load_e over experts whose replica set lies inside S) / |S|, by enumerating all
+ * subsets (G <= 16, else FINE_UNSUPPORTED).   place [n,E,G] uint8 (non-zero = replica);
+ * load [E] int32 -> m_num [n] int64, m_den [n] int32 out: m as a reduced fraction (0 is 0/1).
+ * A placement in which an expert with load has no replica gets m_num = -1, m_den = 0.
+ */
+int fine_eval_placements(const fine_shape* shape, int32_t n, const uint8_t* place, const int32_t* load,
+                         int64_t* m_num, int32_t* m_den, void* stream);
+
+/*
+ * Section 5.3, step 2: draw n random placements with the replica counts `counts` and keep the
+ * one whose m (Eq. 3) is smallest (ties: the lowest candidate index).  G <= 16.
+ * Candidate c is drawn expert by expert, experts with more replicas first (ties: lower
+ * index); an expert's replicas go to the ranks with the most free slots, ties by the larger
+ * key(seed, c, e, g), then the lower rank, where with mix(h) = the 32-bit finaliser of
+ * MurmurHash3 (h ^= h >> 16; h *= 0x85EBCA6B; h ^= h >> 13; h *= 0xC2B2AE35; h ^= h >> 16)
+ *   key = mix( mix(seed + 0x9E3779B9 * (c + 1)) ^ ((64 e + g + 1) * 0x9E3779B1) )   (mod 2^32).
+ * counts [E] must hold values in 1..G that sum to at most G * slots (what
+ * fine_replica_counts writes); other values give a meaningless result, never a fault.
+ *   m_num, m_den [n] out: every candidate's m as in fine_eval_placements;
+ *   best [1] out: index of the chosen candidate; place [E,G] uint8 out: its replica mask.
+ */
+int fine_place_search(const fine_shape* shape, const int32_t* load, const int32_t* counts, int32_t slots,
+                      int32_t n, uint32_t seed, int64_t* m_num, int32_t* m_den, int32_t* best,
+                      uint8_t* place, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

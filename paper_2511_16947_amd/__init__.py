@@ -30,7 +30,8 @@ FLAG_LOCALITY, FLAG_SIMPLE_FFN, FLAG_ONLY_GEMM1, FLAG_ONLY_GEMM2 = 1, 2, 4, 8
 WS_TOPK, WS_SCHED, WS_FFN, WS_BACKWARD = 0, 1, 2, 3
 
 EXPORTS = ["fine_version", "fine_last_hip_error", "fine_workspace_bytes", "fine_topk", "fine_sched",
-           "fine_permute", "fine_grouped_ffn", "fine_combine", "fine_backward"]
+           "fine_permute", "fine_grouped_ffn", "fine_combine", "fine_backward", "fine_replica_counts",
+           "fine_eval_placements", "fine_place_search"]
 
 
 class FineError(RuntimeError):
@@ -77,6 +78,12 @@ def load_library() -> ctypes.CDLL:
     lib.fine_combine.argtypes = [sp, vp, vp, vp, vp, vp]
     lib.fine_backward.restype = ctypes.c_int
     lib.fine_backward.argtypes = [sp, i32] + [vp] * 16 + [ctypes.c_int, vp, sz, vp]
+    lib.fine_replica_counts.restype = ctypes.c_int
+    lib.fine_replica_counts.argtypes = [sp, vp, i32, vp, vp]
+    lib.fine_eval_placements.restype = ctypes.c_int
+    lib.fine_eval_placements.argtypes = [sp, i32, vp, vp, vp, vp, vp]
+    lib.fine_place_search.restype = ctypes.c_int
+    lib.fine_place_search.argtypes = [sp, vp, vp, i32, i32, ctypes.c_uint32, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -178,6 +185,25 @@ def fine_backward(shape: Shape, rank: int, d_out, x_perm, y_perm, act_save, w_ga
                                       _ptr(seg_off), _ptr(topk_w), _ptr(d_x), _ptr(d_topk_w), _ptr(d_w_gate),
                                       _ptr(d_w_up), _ptr(d_w_down), 1 if accumulate else 0, _ptr(ws), ws.numel(), _stream())
     _check("fine_backward", rc)
+
+
+def fine_replica_counts(shape: Shape, load, slots: int, counts):
+    cs = shape.c()
+    _check("fine_replica_counts", load_library().fine_replica_counts(ctypes.byref(cs), _ptr(load), slots, _ptr(counts),
+                                                                     _stream()))
+
+
+def fine_eval_placements(shape: Shape, n: int, place, load, m_num, m_den):
+    cs = shape.c()
+    _check("fine_eval_placements", load_library().fine_eval_placements(ctypes.byref(cs), n, _ptr(place), _ptr(load),
+                                                                       _ptr(m_num), _ptr(m_den), _stream()))
+
+
+def fine_place_search(shape: Shape, load, counts, slots: int, n: int, seed: int, m_num, m_den, best, place):
+    cs = shape.c()
+    rc = load_library().fine_place_search(ctypes.byref(cs), _ptr(load), _ptr(counts), slots, n, seed & 0xFFFFFFFF,
+                                          _ptr(m_num), _ptr(m_den), _ptr(best), _ptr(place), _stream())
+    _check("fine_place_search", rc)
 
 
 # ---------------------------------------------------------------------------

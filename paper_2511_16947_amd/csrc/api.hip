@@ -148,5 +148,30 @@ int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
                            (hipStream_t)stream);
 }
 
+int fine_replica_counts(const fine_shape* shape, const int32_t* load, int32_t slots, int32_t* counts, void* stream) {
+    FINE_TRY(check_shape(shape));
+    if (!load || !counts) return FINE_INVALID_ARG;
+    if (slots < 1 || slots > (1 << 20) || (long long)shape->G * slots < shape->E) return FINE_INVALID_ARG;
+    return launch_replica_counts(*shape, load, slots, counts, (hipStream_t)stream);
+}
+
+int fine_eval_placements(const fine_shape* shape, int32_t n, const uint8_t* place, const int32_t* load,
+                         int64_t* m_num, int32_t* m_den, void* stream) {
+    FINE_TRY(check_shape(shape));
+    if (n < 0 || !load || (n > 0 && (!place || !m_num || !m_den))) return FINE_INVALID_ARG;
+    if (shape->G > 16) return FINE_UNSUPPORTED;
+    return launch_eval_placements(*shape, n, place, load, m_num, m_den, (hipStream_t)stream);
+}
+
+int fine_place_search(const fine_shape* shape, const int32_t* load, const int32_t* counts, int32_t slots,
+                      int32_t n, uint32_t seed, int64_t* m_num, int32_t* m_den, int32_t* best, uint8_t* place,
+                      void* stream) {
+    FINE_TRY(check_shape(shape));
+    if (!load || !counts || !m_num || !m_den || !best || !place) return FINE_INVALID_ARG;
+    if (n < 1 || slots < 1 || slots > (1 << 20) || (long long)shape->G * slots < shape->E) return FINE_INVALID_ARG;
+    if (shape->G > 16) return FINE_UNSUPPORTED;
+    return launch_place_search(*shape, load, counts, slots, n, seed, m_num, m_den, best, place, (hipStream_t)stream);
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -156,4 +156,11 @@ int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, 
                     const float* topk_w, void* d_x, float* d_topk_w, float* d_wg, float* d_wu,
                     float* d_wd, int accumulate, char* ws, hipStream_t st);
 
+
+int launch_replica_counts(const fine_shape& s, const int32_t* load, int slots, int32_t* counts, hipStream_t st);
+int launch_eval_placements(const fine_shape& s, int n, const uint8_t* place, const int32_t* load, int64_t* m_num,
+                           int32_t* m_den, hipStream_t st);
+int launch_place_search(const fine_shape& s, const int32_t* load, const int32_t* counts, int slots, int n, uint32_t seed,
+                        int64_t* m_num, int32_t* m_den, int32_t* best, uint8_t* place, hipStream_t st);
+
 }  // namespace fine

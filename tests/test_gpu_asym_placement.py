@@ -1,0 +1,202 @@
+"""GPU parity of the placement construction from known loads (Section 5.3): replica counts,
+every candidate's score (Eq. 3) and the chosen placement, bit-exact against the oracle."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_16947_amd as fm
+import workloads as wl
+from oracle import placement, sched
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def shape_for(E, G):
+    return fm.Shape(G, 64, 64, E, 1, G, fm.FINE_BF16, 0)
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def gpu_counts(load, E, G, slots):
+    counts = torch.empty(E, dtype=torch.int32, device=DEV)
+    fm.fine_replica_counts(shape_for(E, G), dev_i32(load), slots, counts)
+    torch.cuda.synchronize()
+    return counts
+
+
+def gpu_search(load, counts_dev, E, G, slots, n, seed):
+    m_num = torch.empty(n, dtype=torch.int64, device=DEV)
+    m_den = torch.empty(n, dtype=torch.int32, device=DEV)
+    best = torch.empty(1, dtype=torch.int32, device=DEV)
+    place = torch.empty(E, G, dtype=torch.uint8, device=DEV)
+    fm.fine_place_search(shape_for(E, G), dev_i32(load), counts_dev, slots, n, seed, m_num, m_den, best, place)
+    torch.cuda.synchronize()
+    return m_num.cpu().numpy(), m_den.cpu().numpy(), int(best.cpu()[0]), place.cpu().numpy()
+
+
+def loads_for(kind, E, total, seed):
+    if kind == "zero":
+        return np.zeros(E, dtype=np.int64)
+    if kind == "one_hot":
+        v = np.zeros(E, dtype=np.int64)
+        v[E // 2] = total
+        return v
+    return wl.zipf_loads(E, total, float(kind), seed)
+
+
+# (name, E, G, slots, loads, total, n, seed)
+SEARCH_CASES = [
+    ("tiny", 4, 2, 3, "1.0", 100, 8, 0),
+    ("one_expert", 1, 4, 2, "1.0", 77, 4, 1),
+    ("odd_sizes", 5, 3, 2, "1.5", 1001, 12, 2),
+    ("cfg2_like", 8, 8, 2, "1.0", 16384, 24, 3),
+    ("sec63_zipf13", 32, 8, 8, "1.3", 32768, 32, 0),
+    ("sec63_zipf20", 32, 8, 8, "2.0", 32768, 32, 0),
+    ("many_experts", 128, 8, 24, "1.2", 32768, 6, 4),
+    ("low_bits_boundary", 20, 13, 3, "1.4", 5000, 6, 5),
+    ("one_high_bit", 24, 14, 3, "1.1", 5000, 6, 6),
+    ("cfg5_like_g16", 64, 16, 8, "1.6", 65536, 10, 7),
+    ("g16_no_load", 16, 16, 2, "zero", 0, 3, 8),
+    ("g16_one_hot", 32, 16, 4, "one_hot", 4096, 4, 9),
+    ("spare_slots", 3, 4, 5, "0.5", 999, 5, 10),
+    # few spare replicas: the candidates' scores differ
+    ("one_replica_each", 32, 8, 4, "1.0", 32768, 16, 0),
+    ("tight_g8", 32, 8, 5, "1.3", 32768, 16, 1),
+    ("tight_g16", 64, 16, 5, "1.2", 65536, 8, 2),
+    ("tight_g14", 24, 14, 2, "1.1", 5000, 6, 6),
+    ("tight_g13", 20, 13, 2, "1.4", 5000, 6, 5),
+]
+
+
+@pytest.mark.parametrize("case", SEARCH_CASES, ids=[c[0] for c in SEARCH_CASES])
+def test_counts_scores_and_choice(case):
+    name, E, G, slots, kind, total, n, seed = case
+    print("case", name, flush=True)
+    load = loads_for(kind, E, total, seed)
+    want_counts, want_scores, want_best, want_place = placement.search(load, G, slots, n, seed)
+    counts = gpu_counts(load, E, G, slots)
+    assert np.array_equal(counts.cpu().numpy(), want_counts)
+    m_num, m_den, best, place = gpu_search(load, counts, E, G, slots, n, seed)
+    for c in range(n):
+        assert (int(m_num[c]), int(m_den[c])) == (want_scores[c].numerator, want_scores[c].denominator), c
+    assert best == want_best
+    assert np.array_equal(place, want_place)
+
+
+def test_given_placements_are_scored_by_eq3():
+    rng = np.random.default_rng(0)
+    cases = [
+        (wl.placement_cycle(8), wl.zipf_loads(8, 16384, 1.0, 0)),
+        (wl.placement_z2xz4(), wl.zipf_loads(16, 4096, 1.5, 1)),
+        (wl.placement_complete_plus_matching(8), wl.zipf_loads(32, 32768, 2.0, 2)),
+        (wl.placement_torus4x4(), wl.zipf_loads(32, 8192, 1.2, 3)),
+        (wl.placement_circulant(64, 16), wl.zipf_loads(64, 65536, 2.5, 4)),
+        (wl.placement_full(16, 4), wl.zipf_loads(16, 1000, 1.5, 5)),
+        (wl.placement_home(32, 8), wl.zipf_loads(32, 1024, 1.0, 6)),
+    ]
+    for place, load in cases:
+        E, G = place.shape
+        # the published placement, then hypergraphs: random replica sets of 1 to 4 ranks
+        stack = [place]
+        for _ in range(5):
+            p = np.zeros((E, G), dtype=np.uint8)
+            for e in range(E):
+                p[e, rng.choice(G, size=int(rng.integers(1, min(G, 4) + 1)), replace=False)] = 1
+            stack.append(p)
+        n = len(stack)
+        m_num = torch.empty(n, dtype=torch.int64, device=DEV)
+        m_den = torch.empty(n, dtype=torch.int32, device=DEV)
+        fm.fine_eval_placements(shape_for(E, G), n, torch.from_numpy(np.stack(stack)).to(DEV), dev_i32(load), m_num, m_den)
+        torch.cuda.synchronize()
+        for c in range(n):
+            want = sched.lp_optimum_eq3(load, stack[c])
+            assert (int(m_num[c]), int(m_den[c])) == (want.numerator, want.denominator), (E, G, c)
+
+
+def test_expert_with_load_and_no_replica_is_flagged():
+    place = wl.placement_cycle(8).copy()
+    place[3, :] = 0
+    load = np.arange(1, 9)
+    m_num = torch.empty(2, dtype=torch.int64, device=DEV)
+    m_den = torch.empty(2, dtype=torch.int32, device=DEV)
+    both = np.stack([place, wl.placement_cycle(8)])
+    fm.fine_eval_placements(shape_for(8, 8), 2, torch.from_numpy(both).to(DEV), dev_i32(load), m_num, m_den)
+    torch.cuda.synchronize()
+    assert (int(m_num[0]), int(m_den[0])) == (-1, 0)
+    want = sched.lp_optimum_eq3(load, both[1])
+    assert (int(m_num[1]), int(m_den[1])) == (want.numerator, want.denominator)
+    # no load on that expert: an ordinary placement again
+    load[3] = 0
+    fm.fine_eval_placements(shape_for(8, 8), 1, torch.from_numpy(both[:1].copy()).to(DEV), dev_i32(load), m_num, m_den)
+    torch.cuda.synchronize()
+    want = sched.lp_optimum_eq3(load, place)
+    assert (int(m_num[0]), int(m_den[0])) == (want.numerator, want.denominator)
+
+
+def test_argument_checks():
+    load = dev_i32(np.ones(64))
+    counts = torch.empty(64, dtype=torch.int32, device=DEV)
+    with pytest.raises(fm.FineError) as e:
+        fm.fine_replica_counts(shape_for(64, 16), load, 3, counts)           # 48 slots for 64 experts
+    assert e.value.code == fm.FINE_INVALID_ARG
+    m_num = torch.empty(4, dtype=torch.int64, device=DEV)
+    m_den = torch.empty(4, dtype=torch.int32, device=DEV)
+    best = torch.empty(1, dtype=torch.int32, device=DEV)
+    place = torch.empty(64, 32, dtype=torch.uint8, device=DEV)
+    with pytest.raises(fm.FineError) as e:
+        fm.fine_place_search(shape_for(64, 32), load, counts, 4, 4, 0, m_num, m_den, best, place)   # 2^32 subsets
+    assert e.value.code == fm.FINE_UNSUPPORTED
+    with pytest.raises(fm.FineError) as e:
+        fm.fine_place_search(shape_for(64, 16), load, counts, 4, 0, 0, m_num, m_den, best, place)
+    assert e.value.code == fm.FINE_INVALID_ARG
+    fm.fine_replica_counts(shape_for(64, 32), load, 4, counts)               # counts alone work for any G <= 64
+    torch.cuda.synchronize()
+    assert counts.cpu().tolist() == [2] * 64
+
+
+def test_chosen_placement_feeds_the_scheduler():
+    """Section 6.3's outcome through the library alone: the placement built from the loads
+    lets token scheduling balance completely where the symmetric placement does not, and the
+    scheduler's optimum is the ceiling of the score."""
+    E, G, slots, P = 32, 8, 8, 32768
+    for s in (1.3, 2.0):
+        load = wl.zipf_loads(E, P, s, 0)
+        counts = gpu_counts(load, E, G, slots)
+        m_num, m_den, best, place = gpu_search(load, counts, E, G, slots, 32, 0)
+        idx = np.repeat(np.arange(E, dtype=np.int32), load)
+        np.random.default_rng(1).shuffle(idx)
+        shape = fm.Shape(P, 64, 64, E, 1, G, fm.FINE_BF16, fm.FLAG_LOCALITY)
+        sb = fm.SchedBuffers(shape, DEV)
+        topk = torch.from_numpy(idx.reshape(-1, 1)).to(DEV)
+        sb.run(shape, topk, torch.from_numpy(place).to(DEV))
+        torch.cuda.synchronize()
+        m = Fraction(int(m_num[best]), int(m_den[best]))
+        assert int(sb.max_load.cpu()[0]) == -((-m.numerator) // m.denominator) == P // G
+        sb.run(shape, topk, torch.from_numpy(wl.placement_complete_plus_matching(8)).to(DEV))
+        torch.cuda.synchronize()
+        assert int(sb.max_load.cpu()[0]) > P // G
+
+
+def test_full_size_search_sampled():
+    """The bench's search (config 5's shape: 64 experts, 16 ranks, 80 replica slots, 4096
+    candidates): sampled candidates against the oracle, and the choice
+    against the scores themselves."""
+    E, G, slots, n, seed = 64, 16, 5, 4096, 5
+    load = wl.zipf_loads(E, 65536, 1.2, 5)
+    counts = gpu_counts(load, E, G, slots)
+    assert np.array_equal(counts.cpu().numpy(), placement.replica_counts(load, G, slots))
+    m_num, m_den, best, place = gpu_search(load, counts, E, G, slots, n, seed)
+    scores = [Fraction(int(a), int(b)) for a, b in zip(m_num, m_den)]
+    assert scores[best] == min(scores) and best == scores.index(min(scores))
+    want_counts = counts.cpu().numpy()
+    for c in sorted({0, 1, n - 1, best, 1234, 2048, 3333}):
+        p = placement.draw_placement(want_counts, G, slots, seed, c)
+        assert placement.max_density(load, p) == scores[c], c
+        if c == best:
+            assert np.array_equal(place, p)
+    assert len(set(scores)) > 1
