@@ -7,6 +7,10 @@ FFN for every logical rank (one rank after another), combine; for the training
 workload (cfg5_train) the backward pass as well.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2_mixtral]
+
+    python bench.py --placement-search [--config cfg5_train]
+times the other device path instead, the placement construction from known expert loads
+(Section 5.3): replica counts + 4096 random candidates scored by Eq. 3 + the choice.
 """
 import argparse
 import json
@@ -48,6 +52,10 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (the known-size kernel that HBM byte "
                          "counters are scaled by) and exit")
+    ap.add_argument("--placement-search", action="store_true",
+                    help="time the placement construction from the workload's expert loads instead of the layer")
+    ap.add_argument("--candidates", type=int, default=4096)
+    ap.add_argument("--slots", type=int, default=0, help="replica slots per rank (default: 5 E / (4 G), rounded up)")
     return ap.parse_args()
 
 
@@ -75,6 +83,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": {"bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 5}}))
+        return
+    if args.placement_search:
+        run_placement_search(args, cfg, dev)
         return
     t_gen = time.time()
     inp = wl.make_inputs(cfg, dev)
@@ -273,6 +284,87 @@ def run_cpu_baseline(cfg, inp, topk_idx, topk_w):
             "sample": "dense per-token fp64 layer on the first %d of %d tokens (%.2f s, includes fp64 weight "
                       "conversion); scheduler oracle on the full routing table took %.2f s"
                       % (n, cfg.T, t_ffn, t_sched)}
+
+
+INT32_VECTOR_PEAK_TOPS = 39.3       # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32-bit integer operation per lane and clock
+
+
+def run_placement_search(args, cfg, dev):
+    """A step = fine_replica_counts + fine_place_search on the expert loads that the workload's own
+    gate produces.  Algorithmic work of a candidate: the subset-sum transform behind Eq. 3,
+    G 2^(G-1) integer additions, plus 2^G - 1 exact fraction comparisons (not counted)."""
+    import numpy as np
+    import torch
+
+    import paper_2511_16947_amd as fm
+    import workloads as wl
+    from oracle import placement
+
+    inp = wl.make_inputs(cfg, dev, with_weights=False)
+    shape = fm.shape_of(cfg)
+    topk_idx = torch.empty(cfg.T, cfg.K, dtype=torch.int32, device=dev)
+    topk_w = torch.empty(cfg.T, cfg.K, dtype=torch.float32, device=dev)
+    fm.fine_topk(shape, inp.x, inp.w_router, inp.bias, topk_idx, topk_w)
+    sb = fm.SchedBuffers(shape, dev)
+    sb.run(shape, topk_idx)
+    E, G, n = cfg.E, cfg.G, args.candidates
+    slots = args.slots or -(-5 * E // (4 * G))
+    counts = torch.empty(E, dtype=torch.int32, device=dev)
+    m_num = torch.empty(n, dtype=torch.int64, device=dev)
+    m_den = torch.empty(n, dtype=torch.int32, device=dev)
+    best = torch.empty(1, dtype=torch.int32, device=dev)
+    place = torch.empty(E, G, dtype=torch.uint8, device=dev)
+
+    def step():
+        fm.fine_replica_counts(shape, sb.load, slots, counts)
+        fm.fine_place_search(shape, sb.load, counts, slots, n, 0, m_num, m_den, best, place)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # the search call alone (its scoring kernel dominates; the pick kernel rides along), events on the stream it runs on
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * args.detail_iters)]
+    for i in range(args.detail_iters):
+        ev[2 * i].record()
+        fm.fine_place_search(shape, sb.load, counts, slots, n, 0, m_num, m_den, best, place)
+        ev[2 * i + 1].record()
+    torch.cuda.synchronize()
+    search_ms = float(np.mean([ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(args.detail_iters)]))
+    adds = float(n) * G * 2 ** (G - 1)
+    b = int(best.cpu()[0])
+    line = {
+        "metric": "placement candidates scored per second (Section 5.3 search, Eq. 3 over all rank subsets)",
+        "value": round(n / (ms * 1e-3), 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "%s_loads_placement_search" % cfg.name, "E": E, "G": G, "slots_per_rank": slots,
+                   "candidates": n, "best": b, "m": "%d/%d" % (int(m_num[b]), int(m_den[b])),
+                   "perfect": "%d/%d" % (cfg.T * cfg.K, G)},
+        "roofline": {"bound": "alu", "achieved": round(adds / (search_ms * 1e-3) / 1e12, 3),
+                     "peak": INT32_VECTOR_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": round(adds / (search_ms * 1e-3) / 1e12 / INT32_VECTOR_PEAK_TOPS, 4), "traffic": None,
+                     "kernel": "k_score (+ k_pick) of one fine_place_search call", "ms": round(search_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        load = sb.load.cpu().numpy().astype(np.int64)
+        want_counts = placement.replica_counts(load, G, slots)
+        sample = 0
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < 10.0 and sample < n:
+            p = placement.draw_placement(want_counts, G, slots, 0, sample)
+            m = placement.max_density(load, p)
+            assert (m.numerator, m.denominator) == (int(m_num[sample]), int(m_den[sample])), sample
+            sample += 1
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": round(sample / dt, 2), "unit": "candidates/s", "cores": 1, "kind": "oracle",
+                                "sample": "the first %d of %d candidates drawn and scored by the oracle in %.1f s, each "
+                                          "checked against the device's score" % (sample, n, dt)}
+    print(json.dumps(line))
 
 
 if __name__ == "__main__":

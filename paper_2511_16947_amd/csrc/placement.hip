@@ -5,16 +5,16 @@
 //                      the largest load per replica (exact comparison by cross-multiplication,
 //                      ties to the lower expert index).  One wavefront; the argmax of a round is
 //                      a lane-local scan plus a butterfly over the wave.
-//   k_score            step 2, one block per candidate: wave 0 draws the candidate's placement
-//                      (or reads a given one), the block then evaluates Eq. 3 over all 2^G - 1
-//                      rank subsets.
+//   k_score            step 2, four candidates per block: each wave draws one candidate's placement
+//                      (or the block reads given ones); the block then evaluates Eq. 3 over all
+//                      2^G - 1 rank subsets for one candidate after the other.
 //   k_pick             the candidate with the smallest m (ties: lowest index); draws it again and
 //                      writes it out as a mask [E][G].
 //
 // Eq. 3 over all subsets.  w(S) = sum of load_e over experts whose replica set lies inside S is
 // the subset-sum (zeta) transform of f[mask] = sum of load_e with replica set == mask: for
 // each rank bit b in turn, every S containing b adds the value of S without b.  The table is
-// kept in LDS for the low LOW = min(G, 13) ranks (32 KB, so four blocks share a CU); the
+// kept in LDS for the low min(G, 13) ranks (32 KB, so several blocks share a CU); the
 // remaining high ranks are enumerated: for a pattern h of high ranks, the experts whose high
 // part lies inside h are scattered by their low part, transformed over the low bits, and every
 // entry L gives the candidate w / (popcount(L) + popcount(h)).  Fractions are compared exactly
@@ -22,8 +22,9 @@
 //
 // Drawing a candidate: experts in order of decreasing replica count (ties: lower index); an
 // expert's c replicas go to the c ranks with the most free slots, ties by the larger random
-// key, then the lower rank.  Lane g of wave 0 is rank g: its position in that order is the
-// number of lanes with a larger composite key, one cross-lane read per rank.  The keys come
+// key, then the lower rank.  Lane g of the drawing wave is rank g: its position in that order is
+// the number of lanes with a larger composite key, one cross-lane read per rank.  A single wave
+// draws slowly (a chain of E dependent steps), which is why a block draws four candidates at once.  The keys come
 // from a counter-based generator: two rounds of the MurmurHash3 32-bit finaliser over
 // (seed, candidate) and (expert, rank).
 #include "common.h"
@@ -37,6 +38,7 @@ typedef long long i64;
 
 constexpr int kScoreThreads = 256;
 constexpr int kLowMax = 13;
+constexpr int kCandPerBlock = kScoreThreads / 64;      // one per wave
 constexpr int kMaxE = 1024;
 
 __device__ inline uint32_t mix32(uint32_t h) {
@@ -52,12 +54,12 @@ __device__ inline uint32_t rank_key(uint32_t seed, uint32_t cand, uint32_t e, ui
     return mix32(h ^ ((e * 64u + g + 1u) * 0x9E3779B1u));
 }
 
-// a.num / a.den > b.num / b.den, exactly (den > 0; num < 2^32, den <= 64)
+// a.num / a.den > b.num / b.den, exactly (0 <= num < 2^31: a sum of loads; 0 < den <= 64)
 struct Frac {
-    i64 num;
+    int num;
     int den;
 };
-__device__ inline bool frac_gt(Frac a, Frac b) { return a.num * b.den > b.num * a.den; }
+__device__ inline bool frac_gt(Frac a, Frac b) { return (i64)a.num * b.den > (i64)b.num * a.den; }
 
 // ---------------------------------------------------------------------------
 // step 1
@@ -105,23 +107,25 @@ __global__ __launch_bounds__(64) void k_replica_counts(const int32_t* __restrict
 }
 
 // ---------------------------------------------------------------------------
-// drawing a candidate (wave 0 of the block; lanes >= G idle along)
+// drawing a candidate (one wave; lanes >= G idle along)
 // ---------------------------------------------------------------------------
-// s_order [E]: experts in drawing order; s_mask [E] out: replica set of each expert as a rank mask
-__device__ inline void draw_candidate(const int32_t* __restrict__ counts, const int* s_order, uint32_t* s_mask, int E,
-                                      int G, int slots, uint32_t seed, uint32_t cand) {
-    const int g = threadIdx.x;            // lane = rank
+// s_cnt [E]: replica counts; s_order [E]: experts in drawing order; s_mask [E] out: replica set of
+// each expert as a rank mask
+__device__ inline void draw_candidate(const int* s_cnt, const int* s_order, uint32_t* s_mask, int E, int G, int slots,
+                                      uint32_t seed, uint32_t cand) {
+    const int g = threadIdx.x & 63;       // lane = rank
     int free_slots = slots;
     for (int i = 0; i < E; ++i) {
         const int e = s_order[i];
-        const int c = counts[e];
+        const int c = s_cnt[e];
         // larger is better: free slots, then key, then lower rank; distinct over the ranks
         const u64 comp = g < G ? ((u64)(uint32_t)(free_slots + (1 << 20)) << 40) |
                                      ((u64)rank_key(seed, cand, (uint32_t)e, (uint32_t)g) << 8) | (u64)(255 - g)
                                : 0ull;
         int ahead = 0;
-        for (int j = 0; j < G; ++j) {
-            const u64 other = ((u64)(uint32_t)__shfl((int)(comp >> 32), j, 64) << 32) | (uint32_t)__shfl((int)comp, j, 64);
+        for (int j = 0; j < G; ++j) {      // j is wave-uniform: lane j's value through a scalar register
+            const u64 other = ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(comp >> 32), j) << 32) |
+                              (uint32_t)__builtin_amdgcn_readlane((int)comp, j);
             ahead += other > comp;
         }
         const bool chosen = g < G && ahead < c;
@@ -147,81 +151,17 @@ __device__ inline void drawing_order(const int32_t* __restrict__ counts, int* s_
     __syncthreads();
 }
 
-// ---------------------------------------------------------------------------
-// step 2: score one candidate per block
-// ---------------------------------------------------------------------------
-// DRAW: the candidate is drawn from (counts, slots, seed, blockIdx.x); else read from place[blockIdx.x]
-template <bool DRAW>
-__global__ __launch_bounds__(kScoreThreads) void k_score(const int32_t* __restrict__ load, const int32_t* __restrict__ counts,
-                                                         const uint8_t* __restrict__ place, int E, int G, int slots,
-                                                         uint32_t seed, int64_t* __restrict__ m_num,
-                                                         int32_t* __restrict__ m_den) {
-    extern __shared__ int s_dyn[];
-    const int LOW = min(G, kLowMax);
-    int* s_f = s_dyn;                              // [2^LOW]
-    uint32_t* s_mask = (uint32_t*)(s_f + (1 << LOW));   // [E]
-    int* s_load = (int*)(s_mask + E);              // [E]
-    int* s_order = s_load + E;                     // [E]
-    int* s_cnt = s_order + E;                      // [E]
-    __shared__ i64 s_best_num[kScoreThreads / 64];
-    __shared__ int s_best_den[kScoreThreads / 64];
-    __shared__ int s_bad;
+// Block maximum of the threads' best fractions (any maximiser gives the same reduced fraction),
+// reduced by the gcd and written out; `bad` flags an expert with load and no replica.
+__device__ inline void write_score(Frac best, int bad, int64_t* __restrict__ m_num, int32_t* __restrict__ m_den, int cand) {
+    __shared__ int s_best_num[kScoreThreads / 64], s_best_den[kScoreThreads / 64];
     const int tid = threadIdx.x;
-    const uint32_t cand = blockIdx.x;
-
-    if (tid == 0) s_bad = 0;
-    for (int e = tid; e < E; e += kScoreThreads) s_load[e] = max(load[e], 0);
-    if constexpr (DRAW) {
-        drawing_order(counts, s_cnt, s_order, E);
-        if (tid < 64) draw_candidate(counts, s_order, s_mask, E, G, slots, seed, cand);
-    } else {
-        const uint8_t* pl = place + (size_t)cand * E * G;
-        for (int e = tid; e < E; e += kScoreThreads) {
-            uint32_t m = 0;
-            for (int g = 0; g < G; ++g) m |= (pl[(size_t)e * G + g] != 0 ? 1u : 0u) << g;
-            s_mask[e] = m;
-        }
-    }
-    __syncthreads();
-    for (int e = tid; e < E; e += kScoreThreads)
-        if (s_mask[e] == 0 && s_load[e] > 0) s_bad = 1;      // an expert with load and no replica
-
-    const uint32_t low_mask = (1u << LOW) - 1u;
-    const int n_low = 1 << LOW, n_high = 1 << (G - LOW);
-    Frac best{0, 1};
-    for (int h = 0; h < n_high; ++h) {
-        for (int i = tid; i < n_low; i += kScoreThreads) s_f[i] = 0;
-        __syncthreads();
-        for (int e = tid; e < E; e += kScoreThreads) {
-            const uint32_t m = s_mask[e];
-            if (((m >> LOW) & ~(uint32_t)h) == 0 && s_load[e] > 0) atomicAdd(&s_f[m & low_mask], s_load[e]);
-        }
-        __syncthreads();
-        for (int b = 0; b < LOW; ++b) {
-            const int bit = 1 << b;
-            for (int i = tid; i < n_low / 2; i += kScoreThreads) {
-                const int L = ((i >> b) << (b + 1)) | bit | (i & (bit - 1));
-                s_f[L] += s_f[L ^ bit];
-            }
-            __syncthreads();
-        }
-        const int ph = __popc((uint32_t)h);
-        for (int L = tid; L < n_low; L += kScoreThreads) {
-            const int den = __popc((uint32_t)L) + ph;
-            if (den == 0) continue;
-            const Frac c{(i64)s_f[L], den};
-            if (frac_gt(c, best)) best = c;
-        }
-        __syncthreads();
-    }
-    // block maximum (any maximiser gives the same reduced fraction)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
-        Frac o;
-        o.num = ((i64)__shfl_xor((int)(best.num >> 32), off, 64) << 32) | (uint32_t)__shfl_xor((int)best.num, off, 64);
-        o.den = __shfl_xor(best.den, off, 64);
+        const Frac o{__shfl_xor(best.num, off, 64), __shfl_xor(best.den, off, 64)};
         if (frac_gt(o, best)) best = o;
     }
+    __syncthreads();                                   // the previous candidate's maxima have been read
     if ((tid & 63) == 0) {
         s_best_num[tid >> 6] = best.num;
         s_best_den[tid >> 6] = best.den;
@@ -232,15 +172,162 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(const int32_t* __restri
             const Frac o{s_best_num[w], s_best_den[w]};
             if (frac_gt(o, best)) best = o;
         }
-        i64 a = best.num, b = best.den;
+        int a = best.num, b = best.den;
         while (b != 0) {
-            const i64 t = a % b;
+            const int t = a % b;
             a = b;
             b = t;
         }
-        if (a == 0) a = 1;
-        m_num[cand] = s_bad ? -1 : best.num / a;
-        m_den[cand] = s_bad ? 0 : (int)(best.num == 0 ? 1 : best.den / a);
+        m_num[cand] = bad ? -1 : best.num / a;      // gcd(0, den) = den: zero comes out as 0 / 1
+        m_den[cand] = bad ? 0 : best.den / a;
+    }
+}
+
+// Eq. 3 of one candidate, G <= 12: the whole table of 2^G subsets in LDS, one pass per rank bit.
+__device__ inline Frac max_density_small(int* s_f, const uint32_t* s_mask, const int* s_load, int E, int G) {
+    const int tid = threadIdx.x;
+    const int n = 1 << G;
+    for (int i = tid; i < n; i += kScoreThreads) s_f[i] = 0;
+    __syncthreads();
+    for (int e = tid; e < E; e += kScoreThreads)
+        if (s_load[e] > 0) atomicAdd(&s_f[s_mask[e]], s_load[e]);
+    __syncthreads();
+    for (int b = 0; b < G; ++b) {
+        const int bit = 1 << b;
+        for (int i = tid; i < n / 2; i += kScoreThreads) {
+            const int L = ((i >> b) << (b + 1)) | bit | (i & (bit - 1));
+            s_f[L] += s_f[L ^ bit];
+        }
+        __syncthreads();
+    }
+    Frac best{0, 1};
+    for (int L = tid + 1; L < n; L += kScoreThreads) {
+        const Frac c{s_f[L], (int)__popc((uint32_t)L)};
+        if (frac_gt(c, best)) best = c;
+    }
+    __syncthreads();
+    return best;
+}
+
+// The same for 13 <= G <= 16, with a table over the low 13 ranks transformed in registers: every
+// thread holds 32 entries that differ in five index bits, adds along those bits in registers,
+// and the table goes through LDS only to change which bits are the thread's own.  Three rounds
+// cover the 13 bits: (8..12), (2..6), (0, 1, 7); the last one also compares the finished entries.
+// The table is stored at index ^ (((index >> 8) & 15) << 2), which makes the 64 lanes of every
+// access of the three rounds hit 64 different banks (16 lanes x 16 bytes in the last one).
+__device__ inline int table_slot(int idx) { return idx ^ (((idx >> 8) & 15) << 2); }
+
+template <int BITS>
+__device__ inline void add_along_bits(int (&v)[32]) {
+#pragma unroll
+    for (int b = 0; b < BITS; ++b)
+#pragma unroll
+        for (int j = 0; j < 32; ++j)
+            if (j & (1 << b)) v[j] += v[j ^ (1 << b)];
+}
+
+__device__ inline Frac max_density_13(int* s_f, const uint32_t* s_mask, const int* s_load, int E, int G) {
+    constexpr int LOW = kLowMax, NLOW = 1 << LOW;
+    const int tid = threadIdx.x;
+    // index of register j in the three rounds
+    //   A: bits 8..12 = j;             thread bits 0..7 = tid
+    //   B: bits 2..6 = j;              bits 0,1 = tid 0,1; bits 8..11 = tid 2..5; bit 7 = tid 6; bit 12 = tid 7
+    //   C: bits 0,1 = j 0,1; bit 7 = j 2; bit 6 = j 3; bit 12 = j 4;
+    //                                  bits 2..5 = tid 0..3; bits 8,9 = tid 4,5; bits 10,11 = tid 6,7
+    const int base_b = (tid & 3) | (((tid >> 2) & 15) << 8) | (((tid >> 6) & 1) << 7) | (((tid >> 7) & 1) << 12);
+    const int base_c = ((tid & 15) << 2) | (((tid >> 4) & 3) << 8) | (((tid >> 6) & 3) << 10);
+    const int n_high = 1 << (G - LOW);
+    Frac best{0, 1};
+    int v[32];
+    for (int h = 0; h < n_high; ++h) {
+#pragma unroll
+        for (int j = 0; j < 32; ++j) s_f[tid + 256 * j] = 0;
+        __syncthreads();
+        for (int e = tid; e < E; e += kScoreThreads) {
+            const uint32_t m = s_mask[e];
+            if (((m >> LOW) & ~(uint32_t)h) == 0 && s_load[e] > 0) atomicAdd(&s_f[table_slot((int)(m & (NLOW - 1)))], s_load[e]);
+        }
+        __syncthreads();
+        // round A
+#pragma unroll
+        for (int j = 0; j < 32; ++j) v[j] = s_f[table_slot(tid | (j << 8))];
+        add_along_bits<5>(v);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) s_f[table_slot(tid | (j << 8))] = v[j];
+        __syncthreads();
+        // round B
+#pragma unroll
+        for (int j = 0; j < 32; ++j) v[j] = s_f[table_slot(base_b | (j << 2))];
+        add_along_bits<5>(v);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) s_f[table_slot(base_b | (j << 2))] = v[j];
+        __syncthreads();
+        // round C: 16-byte reads (register bits 0, 1 are the index bits 0, 1, which the swizzle leaves alone)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int idx = base_c | ((q & 1) << 7) | (((q >> 1) & 1) << 6) | (((q >> 2) & 1) << 12);
+            const int4 w = *reinterpret_cast<const int4*>(&s_f[table_slot(idx)]);
+            v[4 * q] = w.x; v[4 * q + 1] = w.y; v[4 * q + 2] = w.z; v[4 * q + 3] = w.w;
+        }
+        add_along_bits<3>(v);
+        // all five register bits are index bits here, so an entry's subset size is that of the
+        // thread's base + the pattern + popcount(j): one comparison per size, on the largest sum
+        const int den0 = __popc((uint32_t)base_c) + __popc((uint32_t)h);
+        int mx[6] = {0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < 32; ++j) mx[__builtin_popcount(j)] = max(mx[__builtin_popcount(j)], v[j]);
+#pragma unroll
+        for (int k = 0; k < 6; ++k) {
+            const Frac c{mx[k], max(den0 + k, 1)};       // size 0 is the empty set, whose sum is 0
+            if (frac_gt(c, best)) best = c;
+        }
+        __syncthreads();
+    }
+    return best;
+}
+
+// ---------------------------------------------------------------------------
+// step 2: a block scores kCandPerBlock candidates, one drawn by each of its waves
+// ---------------------------------------------------------------------------
+// DRAW: candidate c is drawn from (counts, slots, seed, c); else it is place[c].  BIG: G >= 13.
+template <bool DRAW, bool BIG>
+__global__ __launch_bounds__(kScoreThreads) void k_score(const int32_t* __restrict__ load, const int32_t* __restrict__ counts,
+                                                         const uint8_t* __restrict__ place, int n, int E, int G, int slots,
+                                                         uint32_t seed, int64_t* __restrict__ m_num,
+                                                         int32_t* __restrict__ m_den) {
+    extern __shared__ __attribute__((aligned(16))) int s_dyn[];
+    int* s_f = s_dyn;                                                  // [2^min(G, 13)]
+    uint32_t* s_mask = (uint32_t*)(s_f + (1 << min(G, kLowMax)));      // [kCandPerBlock][E]
+    int* s_load = (int*)(s_mask + kCandPerBlock * E);                  // [E]
+    int* s_order = s_load + E;                                         // [E]
+    int* s_cnt = s_order + E;                                          // [E]
+    __shared__ int s_bad[kCandPerBlock];
+    const int tid = threadIdx.x;
+    const int cand0 = blockIdx.x * kCandPerBlock;
+    const int ncand = min(kCandPerBlock, n - cand0);
+
+    if (tid < kCandPerBlock) s_bad[tid] = 0;
+    for (int e = tid; e < E; e += kScoreThreads) s_load[e] = max(load[e], 0);
+    if constexpr (DRAW) {
+        drawing_order(counts, s_cnt, s_order, E);
+        const int w = tid >> 6;
+        if (w < ncand) draw_candidate(s_cnt, s_order, s_mask + w * E, E, G, slots, seed, (uint32_t)(cand0 + w));
+    } else {
+        const uint8_t* pl = place + (size_t)cand0 * E * G;
+        for (int i = tid; i < ncand * E; i += kScoreThreads) {
+            uint32_t m = 0;
+            for (int g = 0; g < G; ++g) m |= (pl[(size_t)i * G + g] != 0 ? 1u : 0u) << g;
+            s_mask[i] = m;
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < ncand * E; i += kScoreThreads)
+        if (s_mask[i] == 0 && s_load[i % E] > 0) s_bad[i / E] = 1;      // an expert with load and no replica
+    for (int c = 0; c < ncand; ++c) {
+        Frac best;
+        if constexpr (BIG) best = max_density_13(s_f, s_mask + c * E, s_load, E, G);
+        else best = max_density_small(s_f, s_mask + c * E, s_load, E, G);
+        write_score(best, s_bad[c], m_num, m_den, cand0 + c);
     }
 }
 
@@ -254,15 +341,18 @@ __global__ __launch_bounds__(256) void k_pick(const int64_t* __restrict__ m_num,
     uint32_t* s_mask = (uint32_t*)s_dyn;     // [E]
     int* s_order = (int*)(s_mask + E);       // [E]
     int* s_cnt = s_order + E;                // [E]
-    __shared__ int s_idx[256];
+    __shared__ int s_idx[256], s_num[256], s_den[256];
     const int tid = threadIdx.x;
     // smallest m, then lowest index; candidates flagged infeasible (den == 0) never win
-    int bi = -1;
+    int bi = -1, bn = 0, bd = 1;
     for (int c = tid; c < n; c += 256) {
-        if (m_den[c] <= 0) continue;
-        if (bi < 0 || m_num[c] * m_den[bi] < m_num[bi] * m_den[c]) bi = c;      // ascending c: strict '<' keeps the lower
+        const int cn = (int)m_num[c], cd = m_den[c];
+        if (cd <= 0) continue;
+        if (bi < 0 || (i64)cn * bd < (i64)bn * cd) {      // ascending c: strict '<' keeps the lower index
+            bi = c; bn = cn; bd = cd;
+        }
     }
-    s_idx[tid] = bi;
+    s_idx[tid] = bi; s_num[tid] = bn; s_den[tid] = bd;
     __syncthreads();
     for (int off = 128; off > 0; off >>= 1) {
         if (tid < off) {
@@ -270,10 +360,12 @@ __global__ __launch_bounds__(256) void k_pick(const int64_t* __restrict__ m_num,
             if (b >= 0) {
                 bool take = a < 0;
                 if (!take) {
-                    const i64 l = m_num[b] * m_den[a], r = m_num[a] * m_den[b];
+                    const i64 l = (i64)s_num[tid + off] * s_den[tid], r = (i64)s_num[tid] * s_den[tid + off];
                     take = l < r || (l == r && b < a);
                 }
-                if (take) s_idx[tid] = b;
+                if (take) {
+                    s_idx[tid] = b; s_num[tid] = s_num[tid + off]; s_den[tid] = s_den[tid + off];
+                }
             }
         }
         __syncthreads();
@@ -285,12 +377,12 @@ __global__ __launch_bounds__(256) void k_pick(const int64_t* __restrict__ m_num,
         return;
     }
     drawing_order(counts, s_cnt, s_order, E);
-    if (tid < 64) draw_candidate(counts, s_order, s_mask, E, G, slots, seed, (uint32_t)best);
+    if (tid < 64) draw_candidate(s_cnt, s_order, s_mask, E, G, slots, seed, (uint32_t)best);
     __syncthreads();
     for (int i = tid; i < E * G; i += 256) place[i] = (uint8_t)((s_mask[i / G] >> (i % G)) & 1u);
 }
 
-size_t score_lds(int E, int G) { return ((size_t)(1 << (G < kLowMax ? G : kLowMax)) + 4 * (size_t)E) * 4; }
+size_t score_lds(int E, int G) { return ((size_t)(1 << (G < kLowMax ? G : kLowMax)) + (kCandPerBlock + 3) * (size_t)E) * 4; }
 
 }  // namespace
 
@@ -303,16 +395,18 @@ int launch_replica_counts(const fine_shape& s, const int32_t* load, int slots, i
 int launch_eval_placements(const fine_shape& s, int n, const uint8_t* place, const int32_t* load, int64_t* m_num,
                            int32_t* m_den, hipStream_t st) {
     if (n == 0) return FINE_OK;
-    hipLaunchKernelGGL(k_score<false>, dim3(n), dim3(kScoreThreads), score_lds(s.E, s.G), st, load, (const int32_t*)nullptr,
-                       place, s.E, s.G, 0, 0u, m_num, m_den);
+    auto k = s.G >= kLowMax ? k_score<false, true> : k_score<false, false>;
+    hipLaunchKernelGGL(k, dim3(cdiv(n, kCandPerBlock)), dim3(kScoreThreads), score_lds(s.E, s.G), st, load,
+                       (const int32_t*)nullptr, place, n, s.E, s.G, 0, 0u, m_num, m_den);
     FINE_LAUNCH_CHECK();
     return FINE_OK;
 }
 
 int launch_place_search(const fine_shape& s, const int32_t* load, const int32_t* counts, int slots, int n, uint32_t seed,
                         int64_t* m_num, int32_t* m_den, int32_t* best, uint8_t* place, hipStream_t st) {
-    hipLaunchKernelGGL(k_score<true>, dim3(n), dim3(kScoreThreads), score_lds(s.E, s.G), st, load, counts,
-                       (const uint8_t*)nullptr, s.E, s.G, slots, seed, m_num, m_den);
+    auto k = s.G >= kLowMax ? k_score<true, true> : k_score<true, false>;
+    hipLaunchKernelGGL(k, dim3(cdiv(n, kCandPerBlock)), dim3(kScoreThreads), score_lds(s.E, s.G), st, load, counts,
+                       (const uint8_t*)nullptr, n, s.E, s.G, slots, seed, m_num, m_den);
     FINE_LAUNCH_CHECK();
     hipLaunchKernelGGL(k_pick, dim3(1), dim3(256), (size_t)3 * s.E * 4, st, m_num, m_den, n, counts, s.E, s.G, slots, seed,
                        best, place);
