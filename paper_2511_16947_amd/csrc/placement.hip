@@ -40,6 +40,7 @@ constexpr int kScoreThreads = 256;
 constexpr int kLowMax = 13;
 constexpr int kCandPerBlock = kScoreThreads / 64;      // one per wave
 constexpr int kMaxE = 1024;
+constexpr int kMaxSearchG = 16;      // Eq. 3 by enumeration: 2^G subsets
 
 __device__ inline uint32_t mix32(uint32_t h) {
     h ^= h >> 16;
@@ -123,7 +124,10 @@ __device__ inline void draw_candidate(const int* s_cnt, const int* s_order, uint
                                      ((u64)rank_key(seed, cand, (uint32_t)e, (uint32_t)g) << 8) | (u64)(255 - g)
                                : 0ull;
         int ahead = 0;
-        for (int j = 0; j < G; ++j) {      // j is wave-uniform: lane j's value through a scalar register
+        // lane j's value through a scalar register; lanes from G on hold 0, which is ahead of nobody
+        static_assert(kMaxSearchG == 16, "unrolled over the ranks");
+#pragma unroll
+        for (int j = 0; j < kMaxSearchG; ++j) {
             const u64 other = ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(comp >> 32), j) << 32) |
                               (uint32_t)__builtin_amdgcn_readlane((int)comp, j);
             ahead += other > comp;
