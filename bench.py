@@ -35,8 +35,8 @@ GEMM1_TRAFFIC_BYTES = {"cfg2_mixtral": int(696886.8 * 1024 * 2.0 + 102406.1 * 10
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="cfg2_mixtral")
     ap.add_argument("--ffn", choices=["per_rank", "fused"], default="per_rank",
                     help="per_rank: one fine_grouped_ffn call per logical rank (default); fused: one call for all")
