@@ -200,3 +200,40 @@ def test_full_size_search_sampled():
         if c == best:
             assert np.array_equal(place, p)
     assert len(set(scores)) > 1
+
+
+def test_layer_under_a_placement_built_from_its_own_loads():
+    """The whole forward path under a restricted placement that the library built from the loads
+    its own gate produced: schedule bit-exact against the oracle under that placement, output
+    against the dense per-token definition, and every rank within one row of the mean."""
+    from gpu_common import GpuLayer, check_schedule_against_oracle, max_rel_err, to64, weights_of_factory
+    from oracle import moe
+    cfg = wl.scaled(wl.CONFIGS["cfg3_finegrained"], name="cfg3_small_asym", T=2048, d=256, f=384, E=32, K=2, G=8)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp)
+    layer.topk()
+    layer.sched()                                   # full placement first: only for the load vector
+    torch.cuda.synchronize()
+    E, G, slots = cfg.E, cfg.G, 8                   # 64 replica slots for 32 experts
+    counts = torch.empty(E, dtype=torch.int32, device=DEV)
+    fm.fine_replica_counts(layer.shape, layer.sb.load, slots, counts)
+    n = 64
+    m_num = torch.empty(n, dtype=torch.int64, device=DEV)
+    m_den = torch.empty(n, dtype=torch.int32, device=DEV)
+    best = torch.empty(1, dtype=torch.int32, device=DEV)
+    place = torch.empty(E, G, dtype=torch.uint8, device=DEV)
+    fm.fine_place_search(layer.shape, layer.sb.load, counts, slots, n, 3, m_num, m_den, best, place)
+    torch.cuda.synchronize()
+    load = layer.sb.load.cpu().numpy().astype(np.int64)
+    want_counts, want_scores, want_best, want_place = placement.search(load, G, slots, n, 3)
+    assert np.array_equal(place.cpu().numpy(), want_place) and int(best.cpu()[0]) == want_best
+    assert place.cpu().numpy().sum() < E * G        # a restricted placement indeed
+
+    layer.forward(place=place)
+    idx = layer.topk_idx.cpu().numpy()
+    check_schedule_against_oracle(layer.sb, idx, E, G, want_place)
+    rows = np.diff(layer.sb.rank_off.cpu().numpy())
+    P = cfg.T * cfg.K
+    assert rows.max() == -(-P // G) == int(layer.sb.max_load.cpu()[0])      # complete balance (Section 6.3)
+    ref = moe.dense_reference_by_expert(to64(inp.x), idx, to64(layer.topk_w), weights_of_factory(inp))
+    assert max_rel_err(to64(layer.out), ref) <= 2e-2
