@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (the known-size kernel that HBM byte "
                          "counters are scaled by) and exit")
+    ap.add_argument("--placement", choices=["full", "searched"], default="full",
+                    help="full: every expert on every rank (default); searched: a restricted placement built by "
+                         "fine_replica_counts + fine_place_search from the loads of the workload's own gate")
     ap.add_argument("--placement-search", action="store_true",
                     help="time the placement construction from the workload's expert loads instead of the layer")
     ap.add_argument("--candidates", type=int, default=4096)
@@ -115,8 +118,30 @@ def main():
     def st_topk():
         fm.fine_topk(s, inp.x, inp.w_router, inp.bias, topk_idx, topk_w)
 
-    def st_sched():
+    def searched_placement():
+        """fine_replica_counts + fine_place_search on the loads of the workload's own gate (Section 5.3)."""
+        slots = args.slots or -(-5 * s.E // (4 * s.G))
+        st_topk()
         sb.run(s, topk_idx, None)
+        counts = torch.empty(s.E, dtype=torch.int32, device=dev)
+        m_num = torch.empty(args.candidates, dtype=torch.int64, device=dev)
+        m_den = torch.empty(args.candidates, dtype=torch.int32, device=dev)
+        best = torch.empty(1, dtype=torch.int32, device=dev)
+        mask = torch.empty(s.E, s.G, dtype=torch.uint8, device=dev)
+        fm.fine_replica_counts(s, sb.load, slots, counts)
+        fm.fine_place_search(s, sb.load, counts, slots, args.candidates, 0, m_num, m_den, best, mask)
+        torch.cuda.synchronize()
+        b = int(best.cpu()[0])
+        return mask, ("built from the gate's loads: %d replica slots per rank, best of %d candidates, m = %d/%d "
+                      "(perfect %d/%d)" % (slots, args.candidates, int(m_num[b]), int(m_den[b]), s.P, s.G))
+
+    place = None
+    placement_note = "every expert on every rank"
+    if args.placement == "searched":
+        place, placement_note = searched_placement()
+
+    def st_sched():
+        sb.run(s, topk_idx, place)
 
     def st_permute():
         fm.fine_permute(s, inp.x, sb.pair_of_row, x_perm)
@@ -232,6 +257,23 @@ def main():
         **gbs,
     }
 
+    # ---- the same per-rank calls under a restricted placement built from the loads (2 or so replica
+    # slots per rank, the regime the paper runs in): every rank then holds the same number of experts
+    if args.placement == "full" and s.G <= 16 and cfg.dtype == "bf16":
+        mask, note = searched_placement()
+        sb.run(s, topk_idx, mask)
+        st_permute()
+        rank_ms_r = [float(np.median(time_ms(lambda r=r: st_ffn_rank(r), it))) for r in range(s.G)]
+        rows_r = np.diff(sb.rank_off.cpu().numpy()).astype(np.int64)
+        detail["restricted_placement"] = {
+            "placement": note,
+            "rank_ffn_ms_max_over_mean": round(max(rank_ms_r) / (sum(rank_ms_r) / s.G), 4),
+            "rank_rows_max_over_mean": round(float(rows_r.max() / rows_r.mean()), 4),
+            "ffn_TFLOPs_per_rank_calls": round(fwd_flop / (sum(rank_ms_r) * 1e-3) / 1e12, 2),
+            "rank_ffn_ms": [round(v, 4) for v in rank_ms_r]}
+        sb.run(s, topk_idx, None)                    # back to the full placement
+        st_permute()
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         cpu_baseline = run_cpu_baseline(cfg, inp, topk_idx, topk_w)
@@ -243,7 +285,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": s.T, "d": s.d, "f": s.f, "E": s.E, "K": s.K, "G": s.G,
-                   "placement": "every expert on every rank", "ffn_calls": args.ffn, "backward": bool(do_bwd),
+                   "placement": placement_note, "ffn_calls": args.ffn, "backward": bool(do_bwd),
                    "pre_activations": (None if not do_bwd else "recomputed" if args.recompute else "saved by the forward pass")},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "detail": detail,
     }
