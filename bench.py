@@ -259,7 +259,7 @@ def main():
 
     # ---- the same per-rank calls under a restricted placement built from the loads (2 or so replica
     # slots per rank, the regime the paper runs in): every rank then holds the same number of experts
-    if args.placement == "full" and s.G <= 16 and cfg.dtype == "bf16":
+    if args.placement == "full" and cfg.dtype == "bf16":
         mask, note = searched_placement()
         sb.run(s, topk_idx, mask)
         st_permute()
@@ -380,17 +380,18 @@ def run_placement_search(args, cfg, dev):
     adds = float(n) * G * 2 ** (G - 1)
     b = int(best.cpu()[0])
     line = {
-        "metric": "placement candidates scored per second (Section 5.3 search, Eq. 3 over all rank subsets)",
+        "metric": "placement candidates scored per second (Section 5.3 search; score = Eq. 3, or M* beyond 16 ranks)",
         "value": round(n / (ms * 1e-3), 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": "%s_loads_placement_search" % cfg.name, "E": E, "G": G, "slots_per_rank": slots,
                    "candidates": n, "best": b, "m": "%d/%d" % (int(m_num[b]), int(m_den[b])),
                    "perfect": "%d/%d" % (cfg.T * cfg.K, G)},
-        "roofline": {"bound": "alu", "achieved": round(adds / (search_ms * 1e-3) / 1e12, 3),
-                     "peak": INT32_VECTOR_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": round(adds / (search_ms * 1e-3) / 1e12 / INT32_VECTOR_PEAK_TOPS, 4), "traffic": None,
-                     "kernel": "k_score (+ k_pick) of one fine_place_search call", "ms": round(search_ms, 4)},
+        # beyond 16 ranks the score comes from integer flows whose work depends on the data: no algorithmic count
+        "roofline": None if G > 16 else {
+            "bound": "alu", "achieved": round(adds / (search_ms * 1e-3) / 1e12, 3), "peak": INT32_VECTOR_PEAK_TOPS,
+            "unit": "TOP/s", "frac": round(adds / (search_ms * 1e-3) / 1e12 / INT32_VECTOR_PEAK_TOPS, 4), "traffic": None,
+            "kernel": "k_score (+ k_pick) of one fine_place_search call", "ms": round(search_ms, 4)},
     }
     if not args.no_cpu_baseline:
         load = sb.load.cpu().numpy().astype(np.int64)

@@ -23,7 +23,10 @@ Readings where the paper is silent:
     still has two free slots;
   * the keys come from a counter-based generator (below) so that any
     implementation draws the same candidates from (seed, candidate index);
-  * among candidates of equal m the lowest index wins.
+  * among candidates of equal m the lowest index wins;
+  * Eq. 3 enumerates 2^G - 1 subsets; for more than 16 ranks the score is the
+    integer optimum M* = ceil(m) of Eq. 1 instead (exact max-flow bisection), so
+    candidates whose m differ by less than one token tie.
 """
 from fractions import Fraction
 
@@ -90,8 +93,15 @@ def draw_placement(counts, G: int, slots: int, seed: int, cand: int) -> np.ndarr
 
 
 def max_density(load, place) -> Fraction:
-    """m of Eq. 3 for one placement."""
-    return sched.lp_optimum_eq3(np.asarray(load, dtype=np.int64), np.asarray(place))
+    """m of Eq. 3 for one placement (G <= 16); M* = ceil(m) for wider ones."""
+    load = np.asarray(load, dtype=np.int64)
+    place = np.asarray(place)
+    if place.shape[1] <= 16:
+        return sched.lp_optimum_eq3(load, place)
+    for e in range(len(load)):
+        if load[e] > 0 and not place[e].any():
+            raise ValueError("expert %d has load but no replica" % e)
+    return Fraction(sched.min_max_load(load, place))
 
 
 def search(load, G: int, slots: int, n: int, seed: int):

@@ -159,7 +159,6 @@ int fine_eval_placements(const fine_shape* shape, int32_t n, const uint8_t* plac
                          int64_t* m_num, int32_t* m_den, void* stream) {
     FINE_TRY(check_shape(shape));
     if (n < 0 || !load || (n > 0 && (!place || !m_num || !m_den))) return FINE_INVALID_ARG;
-    if (shape->G > 16) return FINE_UNSUPPORTED;
     return launch_eval_placements(*shape, n, place, load, m_num, m_den, (hipStream_t)stream);
 }
 
@@ -169,7 +168,6 @@ int fine_place_search(const fine_shape* shape, const int32_t* load, const int32_
     FINE_TRY(check_shape(shape));
     if (!load || !counts || !m_num || !m_den || !best || !place) return FINE_INVALID_ARG;
     if (n < 1 || slots < 1 || slots > (1 << 20) || (long long)shape->G * slots < shape->E) return FINE_INVALID_ARG;
-    if (shape->G > 16) return FINE_UNSUPPORTED;
     return launch_place_search(*shape, load, counts, slots, n, seed, m_num, m_den, best, place, (hipStream_t)stream);
 }
 

@@ -1,0 +1,196 @@
+// One-wavefront integer flows on the placement graph (Section 5.1's graph abstraction): ranks are
+// vertices, an expert with units on rank a and a replica on rank b lets load move from a to b,
+// A[a][b] is the total load that may move a -> b.  With G <= 64 a vertex set is a 64-bit mask and a
+// breadth-first search is a few ballots.  Shared by the scheduler's replica-load solver and by the
+// placement scoring for more than 16 ranks.
+#pragma once
+
+#include "common.h"
+
+namespace fine {
+namespace flow {
+
+constexpr int kW = 64;
+typedef unsigned long long u64;
+
+struct Ctx {
+    int* x;        // [E][G]
+    u64* pm;       // [E] replica masks
+    int* A;        // [G][G+1]
+    int* ld;       // [G]
+    int* path;     // [2*G] edges (from, to)
+    int E, G, AS;  // AS = row stride of A
+};
+
+__device__ inline int lane() { return threadIdx.x; }
+
+__device__ inline int wave_sum_i(int v) {
+#pragma unroll
+    for (int off = kW / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kW);
+    return v;
+}
+__device__ inline int wave_min_i(int v) {
+#pragma unroll
+    for (int off = kW / 2; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off, kW));
+    return v;
+}
+__device__ inline int wave_incl_scan_i(int v) {
+#pragma unroll
+    for (int off = 1; off < kW; off <<= 1) {
+        int o = __shfl_up(v, off, kW);
+        if (lane() >= off) v += o;
+    }
+    return v;
+}
+
+// replicas of expert e whose variables are still free when variable (e_cur, g_cur) is being set
+__device__ inline u64 free_mask(const Ctx& c, int e, int e_cur, int g_cur) {
+    if (e > e_cur) return c.pm[e];
+    if (e == e_cur) return c.pm[e] & ~((2ull << g_cur) - 1ull);
+    return 0ull;
+}
+
+// Move `amount` units of free load from rank a to rank b (experts in ascending order).
+__device__ inline void move_units(const Ctx& c, int a, int b, int amount, int e_cur, int g_cur) {
+    int remaining = amount;
+    for (int base = (e_cur < 0 ? 0 : e_cur); base < c.E && remaining > 0; base += kW) {
+        const int e = base + lane();
+        u64 F = 0ull;
+        int m = 0;
+        if (e < c.E) {
+            F = free_mask(c, e, e_cur, g_cur);
+            if (((F >> a) & 1ull) && ((F >> b) & 1ull)) m = c.x[e * c.G + a];
+        }
+        const int inc = wave_incl_scan_i(m);
+        const int before = inc - m;
+        const int t = max(0, min(m, remaining - before));
+        if (t > 0) {
+            c.x[e * c.G + a] -= t;
+            c.x[e * c.G + b] += t;
+            u64 Fa = F & ~(1ull << a), Fb = F & ~(1ull << b);
+            while (Fa) { int q = __ffsll((long long)Fa) - 1; Fa &= Fa - 1; atomicAdd(&c.A[a * c.AS + q], -t); }
+            while (Fb) { int q = __ffsll((long long)Fb) - 1; Fb &= Fb - 1; atomicAdd(&c.A[b * c.AS + q], t); }
+        }
+        remaining -= min(remaining, __shfl(inc, kW - 1, kW));
+        __syncthreads();
+    }
+    if (lane() == 0) { c.ld[a] -= amount; c.ld[b] += amount; }
+    __syncthreads();
+}
+
+// Breadth-first search from `src` over edges with A > 0.  Stops at the first level that
+// holds a rank of `want` (a per-lane predicate, lane = rank).  Returns the chosen rank
+// (lowest of that level) or -1; *visited_out = every rank reached.  The path src -> ... ->
+// target is written to c.path as (from, to) pairs, its length to *len_out and its smallest
+// capacity to *cap_out.
+__device__ inline int bfs(const Ctx& c, int src, bool want, u64* visited_out, int* len_out, int* cap_out) {
+    const int b = lane();
+    u64 inmask = 0ull;
+    if (b < c.G)
+        for (int a = 0; a < c.G; ++a)
+            if (c.A[a * c.AS + b] > 0) inmask |= 1ull << a;
+    u64 visited = 1ull << src, frontier = visited;
+    int parent = -1, target = -1;
+    while (true) {
+        const u64 hit = inmask & frontier;
+        const bool fresh = (b < c.G) && hit && !((visited >> b) & 1ull);
+        if (fresh) parent = __ffsll((long long)hit) - 1;
+        const u64 next = __ballot(fresh);
+        if (next == 0ull) break;
+        visited |= next;
+        const u64 good = __ballot(fresh && want);
+        if (good) { target = __ffsll((long long)good) - 1; break; }
+        frontier = next;
+    }
+    *visited_out = visited;
+    if (target < 0) return -1;
+    int len = 0, cap = 0x7fffffff, cur = target;
+    while (cur != src) {
+        const int p = __shfl(parent, cur, kW);
+        if (lane() == 0) { c.path[2 * len] = p; c.path[2 * len + 1] = cur; }
+        cap = min(cap, c.A[p * c.AS + cur]);
+        cur = p;
+        ++len;
+    }
+    __syncthreads();
+    *len_out = len;
+    *cap_out = cap;
+    return target;
+}
+
+__device__ inline void push_path(const Ctx& c, int len, int amount, int e_cur, int g_cur) {
+    for (int i = 0; i < len; ++i) move_units(c, c.path[2 * i], c.path[2 * i + 1], amount, e_cur, g_cur);
+}
+
+// Everything on each expert's first replica: fills x, A and the rank loads from the replica masks
+// c.pm and the expert loads (negative reads as 0).  Returns (to every lane) whether some expert with
+// load has no replica.  The arrays must not be in use; ends with a barrier.
+__device__ inline bool start_on_first_replicas(const Ctx& c, const int32_t* __restrict__ load) {
+    const int l = lane();
+    for (int i = l; i < c.G * c.AS; i += kW) c.A[i] = 0;
+    for (int i = l; i < c.G; i += kW) c.ld[i] = 0;
+    for (int i = l; i < c.E * c.G; i += kW) c.x[i] = 0;
+    __syncthreads();
+    int bad = 0;
+    for (int e = l; e < c.E; e += kW) {
+        const u64 m = c.pm[e];
+        const int le = max(load[e], 0);
+        if (m == 0ull) {
+            if (le > 0) bad = 1;
+        } else if (le > 0) {
+            const int first = __ffsll((long long)m) - 1;
+            c.x[e * c.G + first] = le;
+            atomicAdd(&c.ld[first], le);
+            u64 others = m & ~(1ull << first);
+            while (others) { int q = __ffsll((long long)others) - 1; others &= others - 1; atomicAdd(&c.A[first * c.AS + q], le); }
+        }
+    }
+    __syncthreads();
+    return __ballot(bad) != 0ull;
+}
+
+// The optimum value M* = ceil(m) of Eq. 1 for P units in all.  Start with M = ceil(P/G).  While some
+// rank a exceeds M, search from a for a rank below M and push the bottleneck amount along the path.
+// If the search finds none, the reached set S is closed (no expert with load in S has a replica
+// outside S), so Eq. 3 gives the lower bound ceil(load(S)/|S|) > M; M jumps to it.  M only ever moves
+// to lower bounds of the optimum and the loop ends with a feasible flow, hence M = M*.
+__device__ inline int optimum_value(const Ctx& c, int P) {
+    const int l = lane();
+    int M = (P + c.G - 1) / c.G;
+    while (true) {
+        const int mine = (l < c.G) ? c.ld[l] : 0;
+        const u64 over = __ballot(l < c.G && mine > M);
+        if (over == 0ull) break;
+        const int a = __ffsll((long long)over) - 1;
+        u64 visited; int len, cap;
+        const int r = bfs(c, a, (l < c.G) && (mine < M), &visited, &len, &cap);
+        if (r < 0) {
+            const bool in = (l < c.G) && ((visited >> l) & 1ull);
+            const int tot = wave_sum_i(in ? mine : 0);
+            const int cnt = __popcll(visited);
+            M = (tot + cnt - 1) / cnt;
+            continue;
+        }
+        const int amount = min(min(c.ld[a] - M, M - c.ld[r]), cap);
+        push_path(c, len, amount, -1, 0);
+    }
+    return M;
+}
+
+// bytes of LDS behind a Ctx for E experts on G ranks
+__host__ __device__ inline size_t ctx_bytes(int E, int G) { return (size_t)E * 8 + ((size_t)E * G + (size_t)G * (G + 1) + 3 * G + 16) * 4; }
+
+// the arrays of a Ctx laid out from `smem` (8-byte aligned)
+__device__ inline Ctx make_ctx(char* smem, int E, int G) {
+    Ctx c;
+    c.E = E; c.G = G; c.AS = G + 1;
+    c.pm = reinterpret_cast<u64*>(smem);
+    c.x = reinterpret_cast<int*>(smem + (size_t)E * 8);
+    c.A = c.x + (size_t)E * G;
+    c.ld = c.A + (size_t)G * c.AS;
+    c.path = c.ld + G;
+    return c;
+}
+
+}  // namespace flow
+}  // namespace fine

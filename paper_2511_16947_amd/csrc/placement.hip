@@ -27,7 +27,7 @@
 // draws slowly (a chain of E dependent steps), which is why a block draws four candidates at once.  The keys come
 // from a counter-based generator: two rounds of the MurmurHash3 32-bit finaliser over
 // (seed, candidate) and (expert, rank).
-#include "common.h"
+#include "flow_wave.h"
 
 namespace fine {
 
@@ -40,7 +40,7 @@ constexpr int kScoreThreads = 256;
 constexpr int kLowMax = 13;
 constexpr int kCandPerBlock = kScoreThreads / 64;      // one per wave
 constexpr int kMaxE = 1024;
-constexpr int kMaxSearchG = 16;      // Eq. 3 by enumeration: 2^G subsets
+constexpr int kMaxEnumG = 16;        // Eq. 3 by enumeration of 2^G subsets up to here, by flows beyond
 
 __device__ inline uint32_t mix32(uint32_t h) {
     h ^= h >> 16;
@@ -112,7 +112,8 @@ __global__ __launch_bounds__(64) void k_replica_counts(const int32_t* __restrict
 // ---------------------------------------------------------------------------
 // s_cnt [E]: replica counts; s_order [E]: experts in drawing order; s_mask [E] out: replica set of
 // each expert as a rank mask
-__device__ inline void draw_candidate(const int* s_cnt, const int* s_order, uint32_t* s_mask, int E, int G, int slots,
+template <int MAXG, typename MaskT>
+__device__ inline void draw_candidate(const int* s_cnt, const int* s_order, MaskT* s_mask, int E, int G, int slots,
                                       uint32_t seed, uint32_t cand) {
     const int g = threadIdx.x & 63;       // lane = rank
     int free_slots = slots;
@@ -125,9 +126,8 @@ __device__ inline void draw_candidate(const int* s_cnt, const int* s_order, uint
                                : 0ull;
         int ahead = 0;
         // lane j's value through a scalar register; lanes from G on hold 0, which is ahead of nobody
-        static_assert(kMaxSearchG == 16, "unrolled over the ranks");
 #pragma unroll
-        for (int j = 0; j < kMaxSearchG; ++j) {
+        for (int j = 0; j < MAXG; ++j) {
             const u64 other = ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(comp >> 32), j) << 32) |
                               (uint32_t)__builtin_amdgcn_readlane((int)comp, j);
             ahead += other > comp;
@@ -135,7 +135,7 @@ __device__ inline void draw_candidate(const int* s_cnt, const int* s_order, uint
         const bool chosen = g < G && ahead < c;
         free_slots -= chosen;
         const u64 m = __ballot(chosen);
-        if (g == 0) s_mask[e] = (uint32_t)m;
+        if (g == 0) s_mask[e] = (MaskT)m;
     }
 }
 
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(const int32_t* __restri
     if constexpr (DRAW) {
         drawing_order(counts, s_cnt, s_order, E);
         const int w = tid >> 6;
-        if (w < ncand) draw_candidate(s_cnt, s_order, s_mask + w * E, E, G, slots, seed, (uint32_t)(cand0 + w));
+        if (w < ncand) draw_candidate<kMaxEnumG>(s_cnt, s_order, s_mask + w * E, E, G, slots, seed, (uint32_t)(cand0 + w));
     } else {
         const uint8_t* pl = place + (size_t)cand0 * E * G;
         for (int i = tid; i < ncand * E; i += kScoreThreads) {
@@ -336,13 +336,51 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(const int32_t* __restri
 }
 
 // ---------------------------------------------------------------------------
+// step 2 for more than 16 ranks: 2^G subsets cannot be enumerated.  One wavefront per candidate
+// finds M* = ceil(m) with exact integer flows (flow_wave.h) and reports it as M* / 1: candidates
+// whose m differ by less than one token tie.
+// ---------------------------------------------------------------------------
+template <bool DRAW>
+__global__ __launch_bounds__(64) void k_score_flow(const int32_t* __restrict__ load, const int32_t* __restrict__ counts,
+                                                   const uint8_t* __restrict__ place, int E, int G, int slots,
+                                                   uint32_t seed, int64_t* __restrict__ m_num, int32_t* __restrict__ m_den) {
+    extern __shared__ __attribute__((aligned(16))) char s_flow[];
+    flow::Ctx c = flow::make_ctx(s_flow, E, G);
+    int* s_order = reinterpret_cast<int*>(s_flow + flow::ctx_bytes(E, G));      // [E]
+    int* s_cnt = s_order + E;                                                   // [E]
+    const int l = threadIdx.x;
+    const uint32_t cand = blockIdx.x;
+    if constexpr (DRAW) {
+        drawing_order(counts, s_cnt, s_order, E);
+        draw_candidate<64>(s_cnt, s_order, c.pm, E, G, slots, seed, cand);
+    } else {
+        const uint8_t* pl = place + (size_t)cand * E * G;
+        for (int e = l; e < E; e += 64) {
+            flow::u64 m = 0ull;
+            for (int g = 0; g < G; ++g) m |= (flow::u64)(pl[(size_t)e * G + g] != 0) << g;
+            c.pm[e] = m;
+        }
+    }
+    __syncthreads();
+    const bool bad = flow::start_on_first_replicas(c, load);
+    int P = 0;
+    for (int e = l; e < E; e += 64) P += max(load[e], 0);
+    P = flow::wave_sum_i(P);
+    const int M = bad ? -1 : flow::optimum_value(c, P);
+    if (l == 0) {
+        m_num[cand] = M;
+        m_den[cand] = bad ? 0 : 1;
+    }
+}
+
+// ---------------------------------------------------------------------------
 // the best candidate
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_pick(const int64_t* __restrict__ m_num, const int32_t* __restrict__ m_den, int n,
                                               const int32_t* __restrict__ counts, int E, int G, int slots, uint32_t seed,
                                               int32_t* __restrict__ best_out, uint8_t* __restrict__ place) {
-    extern __shared__ int s_dyn[];
-    uint32_t* s_mask = (uint32_t*)s_dyn;     // [E]
+    extern __shared__ __attribute__((aligned(16))) int s_dyn[];
+    u64* s_mask = (u64*)s_dyn;               // [E]
     int* s_order = (int*)(s_mask + E);       // [E]
     int* s_cnt = s_order + E;                // [E]
     __shared__ int s_idx[256], s_num[256], s_den[256];
@@ -381,9 +419,12 @@ __global__ __launch_bounds__(256) void k_pick(const int64_t* __restrict__ m_num,
         return;
     }
     drawing_order(counts, s_cnt, s_order, E);
-    if (tid < 64) draw_candidate(s_cnt, s_order, s_mask, E, G, slots, seed, (uint32_t)best);
+    if (tid < 64) {
+        if (G <= kMaxEnumG) draw_candidate<kMaxEnumG>(s_cnt, s_order, s_mask, E, G, slots, seed, (uint32_t)best);
+        else draw_candidate<64>(s_cnt, s_order, s_mask, E, G, slots, seed, (uint32_t)best);
+    }
     __syncthreads();
-    for (int i = tid; i < E * G; i += 256) place[i] = (uint8_t)((s_mask[i / G] >> (i % G)) & 1u);
+    for (int i = tid; i < E * G; i += 256) place[i] = (uint8_t)((s_mask[i / G] >> (i % G)) & 1ull);
 }
 
 size_t score_lds(int E, int G) { return ((size_t)(1 << (G < kLowMax ? G : kLowMax)) + (kCandPerBlock + 3) * (size_t)E) * 4; }
@@ -399,6 +440,14 @@ int launch_replica_counts(const fine_shape& s, const int32_t* load, int slots, i
 int launch_eval_placements(const fine_shape& s, int n, const uint8_t* place, const int32_t* load, int64_t* m_num,
                            int32_t* m_den, hipStream_t st) {
     if (n == 0) return FINE_OK;
+    if (s.G > kMaxEnumG) {
+        const size_t lds = flow::ctx_bytes(s.E, s.G) + 2 * (size_t)s.E * 4;
+        if (lds > 64 * 1024) return FINE_UNSUPPORTED;
+        hipLaunchKernelGGL(k_score_flow<false>, dim3(n), dim3(64), lds, st, load, (const int32_t*)nullptr, place, s.E, s.G, 0,
+                           0u, m_num, m_den);
+        FINE_LAUNCH_CHECK();
+        return FINE_OK;
+    }
     auto k = s.G >= kLowMax ? k_score<false, true> : k_score<false, false>;
     hipLaunchKernelGGL(k, dim3(cdiv(n, kCandPerBlock)), dim3(kScoreThreads), score_lds(s.E, s.G), st, load,
                        (const int32_t*)nullptr, place, n, s.E, s.G, 0, 0u, m_num, m_den);
@@ -408,11 +457,18 @@ int launch_eval_placements(const fine_shape& s, int n, const uint8_t* place, con
 
 int launch_place_search(const fine_shape& s, const int32_t* load, const int32_t* counts, int slots, int n, uint32_t seed,
                         int64_t* m_num, int32_t* m_den, int32_t* best, uint8_t* place, hipStream_t st) {
-    auto k = s.G >= kLowMax ? k_score<true, true> : k_score<true, false>;
-    hipLaunchKernelGGL(k, dim3(cdiv(n, kCandPerBlock)), dim3(kScoreThreads), score_lds(s.E, s.G), st, load, counts,
-                       (const uint8_t*)nullptr, n, s.E, s.G, slots, seed, m_num, m_den);
+    if (s.G > kMaxEnumG) {
+        const size_t lds = flow::ctx_bytes(s.E, s.G) + 2 * (size_t)s.E * 4;
+        if (lds > 64 * 1024) return FINE_UNSUPPORTED;
+        hipLaunchKernelGGL(k_score_flow<true>, dim3(n), dim3(64), lds, st, load, counts, (const uint8_t*)nullptr, s.E, s.G,
+                           slots, seed, m_num, m_den);
+    } else {
+        auto k = s.G >= kLowMax ? k_score<true, true> : k_score<true, false>;
+        hipLaunchKernelGGL(k, dim3(cdiv(n, kCandPerBlock)), dim3(kScoreThreads), score_lds(s.E, s.G), st, load, counts,
+                           (const uint8_t*)nullptr, n, s.E, s.G, slots, seed, m_num, m_den);
+    }
     FINE_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_pick, dim3(1), dim3(256), (size_t)3 * s.E * 4, st, m_num, m_den, n, counts, s.E, s.G, slots, seed,
+    hipLaunchKernelGGL(k_pick, dim3(1), dim3(256), (size_t)4 * s.E * 4, st, m_num, m_den, n, counts, s.E, s.G, slots, seed,
                        best, place);
     FINE_LAUNCH_CHECK();
     return FINE_OK;

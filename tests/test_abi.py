@@ -59,8 +59,8 @@ def test_null_pointers_are_rejected_without_touching_the_gpu(lib):
     one = ctypes.c_void_p(16)          # any non-null address: the checks below fail before it is used
     assert lib.fine_replica_counts(ctypes.byref(s), one, 1, one, None) == fm.FINE_INVALID_ARG       # 4 slots, 8 experts
     assert lib.fine_place_search(ctypes.byref(s), one, one, 4, 0, 0, one, one, one, one, None) == fm.FINE_INVALID_ARG
-    wide = fm.Shape(256, 128, 256, 64, 2, 32, fm.FINE_F32).c()
-    assert lib.fine_place_search(ctypes.byref(wide), one, one, 4, 8, 0, one, one, one, one, None) == fm.FINE_UNSUPPORTED
+    wide = fm.Shape(256, 128, 256, 1024, 2, 64, fm.FINE_F32).c()     # flow tables of 1024 experts x 64 ranks: no room
+    assert lib.fine_place_search(ctypes.byref(wide), one, one, 32, 8, 0, one, one, one, one, None) == fm.FINE_UNSUPPORTED
     assert lib.fine_eval_placements(ctypes.byref(wide), 1, one, one, one, one, None) == fm.FINE_UNSUPPORTED
     assert lib.fine_eval_placements(ctypes.byref(s), 0, None, one, None, None, None) == fm.FINE_OK    # nothing to score
 

@@ -70,6 +70,12 @@ SEARCH_CASES = [
     ("tight_g16", 64, 16, 5, "1.2", 65536, 8, 2),
     ("tight_g14", 24, 14, 2, "1.1", 5000, 6, 6),
     ("tight_g13", 20, 13, 2, "1.4", 5000, 6, 5),
+    # more than 16 ranks: scored by M* = ceil(m) through integer flows
+    ("flow_g17", 20, 17, 2, "1.2", 3000, 6, 11),
+    ("flow_g24", 48, 24, 3, "1.5", 20000, 6, 12),
+    ("flow_cfg4_like_g32", 256, 32, 10, "1.0", 32768, 4, 13),
+    ("flow_g32_tight", 64, 32, 2, "1.3", 32768, 6, 14),
+    ("flow_g64", 64, 64, 2, "1.1", 10000, 3, 15),
 ]
 
 
@@ -98,6 +104,8 @@ def test_given_placements_are_scored_by_eq3():
         (wl.placement_circulant(64, 16), wl.zipf_loads(64, 65536, 2.5, 4)),
         (wl.placement_full(16, 4), wl.zipf_loads(16, 1000, 1.5, 5)),
         (wl.placement_home(32, 8), wl.zipf_loads(32, 1024, 1.0, 6)),
+        (wl.placement_circulant(256, 32), wl.zipf_loads(256, 32768, 1.0, 7)),       # 32 ranks: M* through flows
+        (wl.placement_circulant(64, 32), wl.zipf_loads(64, 4096, 1.6, 8)),
     ]
     for place, load in cases:
         E, G = place.shape
@@ -114,7 +122,7 @@ def test_given_placements_are_scored_by_eq3():
         fm.fine_eval_placements(shape_for(E, G), n, torch.from_numpy(np.stack(stack)).to(DEV), dev_i32(load), m_num, m_den)
         torch.cuda.synchronize()
         for c in range(n):
-            want = sched.lp_optimum_eq3(load, stack[c])
+            want = placement.max_density(load, stack[c])
             assert (int(m_num[c]), int(m_den[c])) == (want.numerator, want.denominator), (E, G, c)
 
 
@@ -148,8 +156,9 @@ def test_argument_checks():
     m_den = torch.empty(4, dtype=torch.int32, device=DEV)
     best = torch.empty(1, dtype=torch.int32, device=DEV)
     place = torch.empty(64, 32, dtype=torch.uint8, device=DEV)
-    with pytest.raises(fm.FineError) as e:
-        fm.fine_place_search(shape_for(64, 32), load, counts, 4, 4, 0, m_num, m_den, best, place)   # 2^32 subsets
+    big = torch.empty(1024, dtype=torch.int32, device=DEV)
+    with pytest.raises(fm.FineError) as e:      # the flow tables of 1024 experts x 64 ranks do not fit
+        fm.fine_place_search(shape_for(1024, 64), big, big, 32, 4, 0, m_num, m_den, best, place)
     assert e.value.code == fm.FINE_UNSUPPORTED
     with pytest.raises(fm.FineError) as e:
         fm.fine_place_search(shape_for(64, 16), load, counts, 4, 0, 0, m_num, m_den, best, place)
