@@ -8,6 +8,8 @@
 //   k_score            step 2, four candidates per block: each wave draws one candidate's placement
 //                      (or the block reads given ones); the block then evaluates Eq. 3 over all
 //                      2^G - 1 rank subsets for one candidate after the other.
+//   k_score_flow       the same for more than 16 ranks, where the subsets cannot be enumerated: one
+//                      wavefront per candidate finds M* = ceil(m) with exact integer flows.
 //   k_pick             the candidate with the smallest m (ties: lowest index); draws it again and
 //                      writes it out as a mask [E][G].
 //
