@@ -52,36 +52,54 @@ __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, con
             k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(d / BK, smem, acc, la, lb, k_tile);
         }
         constexpr int WMC = (BM * (BN * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
-        stage_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(
-            smem, [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; },
-            [&](int m, int c, uint2 dh4) {
-                const int col = n0 + c;
-                if (m >= te.rows || col >= f) return;
+        struct PreAct {
+            uint2 a4, b4;
+        };
+        auto fetch_act = [&](int m, int c) {
+            PreAct p{make_uint2(0u, 0u), make_uint2(0u, 0u)};
+            const int col = n0 + c;
+            if (m < te.rows && col < f) {
                 const size_t row = (size_t)te.row0 + m;
-                const uint2 a4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + col);
-                const uint2 b4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + f + col);
-                const uint32_t dhw[2] = {dh4.x, dh4.y}, aw[2] = {a4.x, a4.y}, bw[2] = {b4.x, b4.y};
-                uint32_t da[2], db[2], hh[2];
+                p.a4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + col);
+                p.b4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + f + col);
+            }
+            return p;
+        };
+        auto swiglu_bwd = [&](int m, int c, uint2 dh4, uint2 a4, uint2 b4) {
+            const int col = n0 + c;
+            if (m >= te.rows || col >= f) return;
+            const size_t row = (size_t)te.row0 + m;
+            const uint32_t dhw[2] = {dh4.x, dh4.y}, aw[2] = {a4.x, a4.y}, bw[2] = {b4.x, b4.y};
+            uint32_t da[2], db[2], hh[2];
 #pragma unroll
-                for (int w = 0; w < 2; ++w) {
-                    float o_da[2], o_db[2], o_h[2];
+            for (int w = 0; w < 2; ++w) {
+                float o_da[2], o_db[2], o_h[2];
 #pragma unroll
-                    for (int hlf = 0; hlf < 2; ++hlf) {
-                        const float dh = bf16_bits_to_float((uint16_t)(dhw[w] >> (16 * hlf)));
-                        const float a = bf16_bits_to_float((uint16_t)(aw[w] >> (16 * hlf)));
-                        const float b = bf16_bits_to_float((uint16_t)(bw[w] >> (16 * hlf)));
-                        const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-a));
-                        o_da[hlf] = dh * b * sg * (1.f + a * (1.f - sg));
-                        o_db[hlf] = dh * a * sg;
-                        o_h[hlf] = a * sg * b;
-                    }
-                    da[w] = pack_bf16x2(o_da[0], o_da[1]);
-                    db[w] = pack_bf16x2(o_db[0], o_db[1]);
-                    hh[w] = pack_bf16x2(o_h[0], o_h[1]);
+                for (int hlf = 0; hlf < 2; ++hlf) {
+                    const float dh = bf16_bits_to_float((uint16_t)(dhw[w] >> (16 * hlf)));
+                    const float a = bf16_bits_to_float((uint16_t)(aw[w] >> (16 * hlf)));
+                    const float b = bf16_bits_to_float((uint16_t)(bw[w] >> (16 * hlf)));
+                    const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-a));
+                    o_da[hlf] = dh * b * sg * (1.f + a * (1.f - sg));
+                    o_db[hlf] = dh * a * sg;
+                    o_h[hlf] = a * sg * b;
                 }
-                *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + col) = make_uint2(da[0], da[1]);
-                *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + f + col) = make_uint2(db[0], db[1]);
-                *reinterpret_cast<uint2*>(h + row * (size_t)f + col) = make_uint2(hh[0], hh[1]);
+                da[w] = pack_bf16x2(o_da[0], o_da[1]);
+                db[w] = pack_bf16x2(o_db[0], o_db[1]);
+                hh[w] = pack_bf16x2(o_h[0], o_h[1]);
+            }
+            *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + col) = make_uint2(da[0], da[1]);
+            *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + f + col) = make_uint2(db[0], db[1]);
+            *reinterpret_cast<uint2*>(h + row * (size_t)f + col) = make_uint2(hh[0], hh[1]);
+        };
+        auto acc_val = [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; };
+        if constexpr (W8)
+            stage_tile_bf16_fetch<WAVES_M, WAVES_N, WM, WN, WMC>(
+                smem, acc_val, fetch_act, [&](int m, int c, uint2 dh4, const PreAct& p) { swiglu_bwd(m, c, dh4, p.a4, p.b4); });
+        else
+            stage_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(smem, acc_val, [&](int m, int c, uint2 dh4) {
+                const PreAct p = fetch_act(m, c);
+                swiglu_bwd(m, c, dh4, p.a4, p.b4);
             });
     }
 }

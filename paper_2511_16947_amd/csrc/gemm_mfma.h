@@ -199,6 +199,55 @@ __device__ inline void stage_tile_bf16(char* smem, Val val, Emit emit) {
     });
 }
 
+// The same for an epilogue that also reads global memory: fetch(row, col) starts the reads of a
+// group of four columns and returns what they deliver, emit(row, col, values, fetched) uses them.
+// The reads of eight groups are started before the first is used, so a thread waits for memory
+// twice per pass instead of once per group.
+template <int WAVES_M, int WAVES_N, int WM, int NT, int WMC, typename Val, typename Fetch, typename Emit>
+__device__ inline void stage_tile_bf16_fetch(char* smem, Val val, Fetch fetch, Emit emit) {
+    constexpr int BNC = WAVES_N * NT * 32;
+    constexpr int PITCH = BNC * 2 + 8;
+    constexpr int ROWS_PASS = WAVES_M * WMC * 32;
+    constexpr int UNITS = ROWS_PASS * (BNC / 4);          // 8-byte units per pass
+    constexpr int THREADS = WAVES_M * WAVES_N * 64;
+    constexpr int AHEAD = 8;
+    static_assert(UNITS % (THREADS * AHEAD) == 0, "whole groups of units per thread");
+    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
+    static_for<WM / WMC>([&](auto pass) {
+        static_for<WMC>([&](auto ml) {
+            constexpr int mi = pass.value * WMC + ml.value;
+            const int crow = (wm * WMC + ml.value) * 32 + acc_m();
+            static_for<NT>([&](auto t) {
+                static_for<4>([&](auto rg) {
+                    const int col = (wn * NT + t.value) * 32 + acc_n(rg.value);
+                    uint2 v;
+                    v.x = pack_bf16x2(val(IntC<mi>{}, t, rg, IntC<0>{}), val(IntC<mi>{}, t, rg, IntC<1>{}));
+                    v.y = pack_bf16x2(val(IntC<mi>{}, t, rg, IntC<2>{}), val(IntC<mi>{}, t, rg, IntC<3>{}));
+                    *reinterpret_cast<uint2*>(smem + crow * PITCH + col * 2) = v;
+                });
+            });
+        });
+        __syncthreads();
+        for (int u0 = threadIdx.x; u0 < UNITS; u0 += THREADS * AHEAD) {
+            auto row_of = [&](int u) {
+                const int crow = u / (BNC / 4);
+                return ((crow / (WMC * 32)) * WM + pass.value * WMC) * 32 + crow % (WMC * 32);
+            };
+            decltype(fetch(0, 0)) got[AHEAD];
+            static_for<AHEAD>([&](auto j) {
+                const int u = u0 + j.value * THREADS;
+                got[j.value] = fetch(row_of(u), (u % (BNC / 4)) * 4);
+            });
+            static_for<AHEAD>([&](auto j) {
+                const int u = u0 + j.value * THREADS;
+                const int crow = u / (BNC / 4), cu = u % (BNC / 4);
+                emit(row_of(u), cu * 4, *reinterpret_cast<const uint2*>(smem + crow * PITCH + cu * 8), got[j.value]);
+            });
+        }
+        __syncthreads();
+    });
+}
+
 // The plain case: the staged values go to C[row0 + row][col0 + col].
 template <int WAVES_M, int WAVES_N, int WM, int NT, int WMC, typename Val>
 __device__ inline void store_tile_bf16(char* smem, Val val, uint16_t* __restrict__ C, size_t ldc, int row0,
