@@ -246,27 +246,20 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
             k_loop<WAVES_M, WAVES_N, WM, WN, (WM * WN >= 16 ? 1 : 2)>(nk, smem, acc, la, lb, k_tile);
         }
         float* out = p.out + (size_t)e * p.M * p.N;
-        // each lane owns four consecutive columns of a row: 16-byte stores
-        static_for<WM>([&](auto mi) {
-            const int m = m0 + (wm * WM + mi.value) * 32 + acc_m();
-            if (m < p.M) {
-                static_for<WN>([&](auto ni) {
-                    static_for<4>([&](auto rg) {
-                        const int col = n0 + (wn * WN + ni.value) * 32 + acc_n(rg.value);
-                        if (col < p.N) {
-                            float4* dst = reinterpret_cast<float4*>(out + (size_t)m * p.N + col);
-                            float4 v = make_float4(acc[mi.value][ni.value][4 * rg.value], acc[mi.value][ni.value][4 * rg.value + 1],
-                                                   acc[mi.value][ni.value][4 * rg.value + 2], acc[mi.value][ni.value][4 * rg.value + 3]);
-                            if (accumulate) {
-                                const float4 o = *dst;
-                                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                            }
-                            *dst = v;
-                        }
-                    });
-                });
-            }
-        });
+        // through LDS, so that a wave stores 1 KB of one row at a time
+        stage_tile_f32<WAVES_M, WAVES_N, WM, WN>(
+            smem, acc,
+            [&](int r, int c) {
+                const int m = m0 + r, col = n0 + c;
+                if (accumulate && m < p.M && col < p.N) return *reinterpret_cast<const float4*>(out + (size_t)m * p.N + col);
+                return make_float4(0.f, 0.f, 0.f, 0.f);
+            },
+            [&](int r, int c, float4 v, float4 o) {
+                const int m = m0 + r, col = n0 + c;
+                if (m >= p.M || col >= p.N) return;
+                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                *reinterpret_cast<float4*>(out + (size_t)m * p.N + col) = v;
+            });
     }
 }
 

@@ -168,6 +168,13 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
 // the 8-byte LDS writes of 32 lanes over all banks); emit(row, col, four bf16) is then called
 // once for every group of four columns.  Every wave must have finished reading the operand
 // tiles in `smem` before the call; on return `smem` may be reused.
+// Barrier between LDS phases of an epilogue: every wave's LDS accesses have completed; global
+// stores stay in flight (__syncthreads() would also wait for them to drain, a microsecond or two
+// per call with a tile's worth of stores outstanding).
+__device__ inline void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 template <int WAVES_M, int WAVES_N, int WM, int NT, int WMC, typename Val, typename Emit>
 __device__ inline void stage_tile_bf16(char* smem, Val val, Emit emit) {
     constexpr int BNC = WAVES_N * NT * 32;
@@ -189,13 +196,13 @@ __device__ inline void stage_tile_bf16(char* smem, Val val, Emit emit) {
                 });
             });
         });
-        __syncthreads();
+        lds_barrier();
         for (int u = threadIdx.x; u < UNITS; u += WAVES_M * WAVES_N * 64) {
             const int crow = u / (BNC / 4), cu = u % (BNC / 4);
             const int row = ((crow / (WMC * 32)) * WM + pass.value * WMC) * 32 + crow % (WMC * 32);
             emit(row, cu * 4, *reinterpret_cast<const uint2*>(smem + crow * PITCH + cu * 8));
         }
-        __syncthreads();
+        lds_barrier();
     });
 }
 
@@ -227,7 +234,7 @@ __device__ inline void stage_tile_bf16_fetch(char* smem, Val val, Fetch fetch, E
                 });
             });
         });
-        __syncthreads();
+        lds_barrier();
         for (int u0 = threadIdx.x; u0 < UNITS; u0 += THREADS * AHEAD) {
             auto row_of = [&](int u) {
                 const int crow = u / (BNC / 4);
@@ -244,7 +251,49 @@ __device__ inline void stage_tile_bf16_fetch(char* smem, Val val, Fetch fetch, E
                 emit(row_of(u), cu * 4, *reinterpret_cast<const uint2*>(smem + crow * PITCH + cu * 8), got[j.value]);
             });
         }
-        __syncthreads();
+        lds_barrier();
+    });
+}
+
+// fp32 tiles (weight gradients): one 32-row fragment row per wave row and pass goes through LDS
+// (rows of BN floats + 16 bytes, so that the 16-byte writes of 16 lanes cover all banks), then
+// emit(row, col, four values) is called with a wave covering 256 consecutive floats of one row:
+// 16-byte stores that fill whole cache lines instead of 32-byte pieces of 32 different rows.
+// fetch(row, col) may start a read of the four old values (accumulation); all of a pass's reads
+// are started before the first is used.
+template <int WAVES_M, int WAVES_N, int WM, int WN, typename Fetch, typename Emit>
+__device__ inline void stage_tile_f32(char* smem, const f32x16 (&acc)[WM][WN], Fetch fetch, Emit emit) {
+    constexpr int BN = WAVES_N * WN * 32;
+    constexpr int PITCH = BN * 4 + 16;
+    constexpr int THREADS = WAVES_M * WAVES_N * 64;
+    constexpr int UNITS = WAVES_M * 32 * (BN / 4);        // 16-byte units per pass
+    static_assert(UNITS % THREADS == 0, "whole units per thread");
+    constexpr int PER = UNITS / THREADS;
+    const int wave = threadIdx.x >> 6, wm = wave / WAVES_N, wn = wave % WAVES_N;
+    static_for<WM>([&](auto mi) {
+        const int crow = wm * 32 + acc_m();
+        static_for<WN>([&](auto ni) {
+            static_for<4>([&](auto rg) {
+                const int col = (wn * WN + ni.value) * 32 + acc_n(rg.value);
+                const f32x16& a = acc[mi.value][ni.value];
+                *reinterpret_cast<float4*>(smem + crow * PITCH + col * 4) =
+                    make_float4(a[4 * rg.value], a[4 * rg.value + 1], a[4 * rg.value + 2], a[4 * rg.value + 3]);
+            });
+        });
+        lds_barrier();
+        float4 old[PER];
+        static_for<PER>([&](auto j) {
+            const int u = threadIdx.x + j.value * THREADS;
+            const int cr = u / (BN / 4);
+            old[j.value] = fetch(((cr / 32) * WM + mi.value) * 32 + cr % 32, (u % (BN / 4)) * 4);
+        });
+        static_for<PER>([&](auto j) {
+            const int u = threadIdx.x + j.value * THREADS;
+            const int cr = u / (BN / 4), cu = u % (BN / 4);
+            emit(((cr / 32) * WM + mi.value) * 32 + cr % 32, cu * 4,
+                 *reinterpret_cast<const float4*>(smem + cr * PITCH + cu * 16), old[j.value]);
+        });
+        lds_barrier();
     });
 }
 
