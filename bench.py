@@ -52,6 +52,8 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain device copy of 1 GiB five times (the known-size kernel that HBM byte "
                          "counters are scaled by) and exit")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph (after the warm-up steps) and time replays of it")
     ap.add_argument("--placement", choices=["full", "searched"], default="full",
                     help="full: every expert on every rank (default); searched: a restricted placement built by "
                          "fine_replica_counts + fine_place_search from the loads of the workload's own gate")
@@ -174,9 +176,24 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        # the library allocates nothing, synchronises nothing and clears its own counters in kernels: a
+        # step is captured as it is
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        run_step = graph.replay
+        for _ in range(3):
+            run_step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -285,7 +302,7 @@ def main():
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": s.T, "d": s.d, "f": s.f, "E": s.E, "K": s.K, "G": s.G,
-                   "placement": placement_note, "ffn_calls": args.ffn, "backward": bool(do_bwd),
+                   "placement": placement_note, "ffn_calls": args.ffn, "launch": "HIP graph replay" if args.graph else "eager", "backward": bool(do_bwd),
                    "pre_activations": (None if not do_bwd else "recomputed" if args.recompute else "saved by the forward pass")},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "detail": detail,
     }

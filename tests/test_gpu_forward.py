@@ -214,3 +214,43 @@ def test_bad_arguments_return_errors():
     with pytest.raises(fm.FineError) as ei:
         fm.fine_grouped_ffn(s, 0, xp, xp, xp, xp, idx, xp, None, torch.zeros(1024, dtype=torch.uint8, device=DEV))
     assert ei.value.code == fm.FINE_WORKSPACE_TOO_SMALL
+
+
+@pytest.mark.parametrize("restricted", [False, True])
+def test_a_step_can_be_captured_in_a_graph(restricted):
+    """The library allocates nothing, synchronises nothing and clears its own counters in kernels,
+    so a whole forward step is captured in a HIP graph as it is.  Every replay, with eager work and
+    synchronisations in between, must give the bits of the eager run."""
+    cfg = wl.LayerConfig("graph_k_cut", 512, 256, 2560, 4, 2, 2, "bf16", 11, "scaled_z", 1.0)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (3 << 8))
+    place = None
+    if restricted:
+        place = torch.from_numpy(np.array([[1, 0], [1, 1], [0, 1], [1, 1]], dtype=np.uint8)).to(DEV)
+    layer.forward(place=place, per_rank=True)             # eager; also sets every kernel attribute before the capture
+    want_out, want_y = layer.out.clone(), layer.y_perm.clone()
+    want_rows = layer.sb.row_of_pair.clone()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            layer.topk()
+            layer.sched(place)
+            layer.permute()
+            for r in range(cfg.G):
+                layer.ffn(r)
+            layer.combine()
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(4):
+        layer.out.zero_()
+        layer.y_perm.zero_()
+        layer.sb.row_of_pair.fill_(-7)
+        layer.topk()                                       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(layer.sb.row_of_pair, want_rows), i
+        assert torch.equal(layer.y_perm.view(torch.int16), want_y.view(torch.int16)), i
+        assert torch.equal(layer.out.view(torch.int16), want_out.view(torch.int16)), i
