@@ -61,6 +61,7 @@ __device__ inline void move_units(const Ctx& c, int a, int b, int amount, int e_
             F = free_mask(c, e, e_cur, g_cur);
             if (((F >> a) & 1ull) && ((F >> b) & 1ull)) m = c.x[e * c.G + a];
         }
+        if (__ballot(m > 0) == 0ull) continue;        // no expert of this chunk links a to b (wave-uniform)
         const int inc = wave_incl_scan_i(m);
         const int before = inc - m;
         const int t = max(0, min(m, remaining - before));

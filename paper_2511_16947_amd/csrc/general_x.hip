@@ -32,23 +32,22 @@ using namespace flow;
 // replicas `later`, lowest first) to rank g.  Variable (e,g) itself is not free, so only
 // the rows of the source ranks change in A.
 __device__ void pull_expert(const Ctx& c, int e, int g, u64 later, u64 from, int amount) {
-    if (lane() == 0) {
-        int rem = amount;
-        u64 L = from;
-        while (L && rem > 0) {
-            const int q = __ffsll((long long)L) - 1;
-            L &= L - 1;
-            const int t = min(rem, c.x[e * c.G + q]);
-            if (t > 0) {
-                c.x[e * c.G + q] -= t;
-                c.x[e * c.G + g] += t;
-                c.ld[q] -= t;
-                c.ld[g] += t;
-                u64 others = later & ~(1ull << q);
-                while (others) { int r = __ffsll((long long)others) - 1; others &= others - 1; c.A[q * c.AS + r] -= t; }
-                rem -= t;
-            }
-        }
+    // lane q = source rank q: what the lower sources leave of `amount` is a prefix sum away
+    const int q = lane();
+    const bool src = q < c.G && ((from >> q) & 1ull);
+    const int m = src ? c.x[e * c.G + q] : 0;
+    const int before = wave_incl_scan_i(m) - m;
+    const int t = max(0, min(m, amount - before));
+    if (t > 0) {
+        c.x[e * c.G + q] -= t;
+        c.ld[q] -= t;
+        u64 others = later & ~(1ull << q);            // row q of A belongs to this lane alone
+        while (others) { int r = __ffsll((long long)others) - 1; others &= others - 1; c.A[q * c.AS + r] -= t; }
+    }
+    const int total = wave_sum_i(t);
+    if (q == 0) {                                      // g is not among the later replicas: nobody else writes these
+        c.x[e * c.G + g] += total;
+        c.ld[g] += total;
     }
     __syncthreads();
 }
@@ -85,19 +84,16 @@ __global__ __launch_bounds__(64) void k_general_x(const uint8_t* __restrict__ pl
         while (todo) {
             const int g = __ffsll((long long)todo) - 1;
             todo &= todo - 1;
-            // variable (e,g) leaves the free set
-            if (l == 0) {
-                u64 others = F & ~(1ull << g);
-                const int xg = c.x[e * G + g];
-                while (others) {
-                    int q = __ffsll((long long)others) - 1; others &= others - 1;
-                    c.A[g * c.AS + q] -= xg;
-                    c.A[q * c.AS + g] -= c.x[e * G + q];
-                }
-            }
+            // variable (e,g) leaves the free set: its units can no longer move to the other free
+            // replicas, nor theirs to g (lane q updates the two entries that involve replica q)
             F &= ~(1ull << g);
-            __syncthreads();
             const u64 later = F;
+            if (later == 0ull) continue;        // the last replica: nothing left to take units from
+            if (l < G && ((later >> l) & 1ull)) {
+                c.A[g * c.AS + l] -= c.x[e * G + g];
+                c.A[l * c.AS + g] -= c.x[e * G + l];
+            }
+            __syncthreads();
             while (true) {
                 int avail = 0;
                 if (l < G && ((later >> l) & 1ull)) avail = c.x[e * G + l];
