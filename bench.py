@@ -357,7 +357,6 @@ def run_placement_search(args, cfg, dev):
 
     import paper_2511_16947_amd as fm
     import workloads as wl
-    from oracle import placement
 
     inp = wl.make_inputs(cfg, dev, with_weights=False)
     shape = fm.shape_of(cfg)
@@ -411,6 +410,8 @@ def run_placement_search(args, cfg, dev):
             "kernel": "k_score (+ k_pick) of one fine_place_search call", "ms": round(search_ms, 4)},
     }
     if not args.no_cpu_baseline:
+        from oracle import placement      # the oracle is used by this baseline leg only
+
         load = sb.load.cpu().numpy().astype(np.int64)
         want_counts = placement.replica_counts(load, G, slots)
         sample = 0
