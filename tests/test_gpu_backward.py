@@ -77,6 +77,35 @@ def test_backward_elementwise(cfg, tile, saved):
         assert max_rel_err(to64(bwd.d_wd), 2.0 * to64(before)) <= 1e-6
 
 
+@pytest.mark.parametrize("tile", [0, 3])
+def test_backward_under_a_restricted_placement(tile):
+    """Scheduling only relocates work (Section 3): under a restricted placement, where an expert's
+    rows sit on several ranks in other proportions, the gradients are those of the dense
+    definition all the same, and the weight gradients of an expert are summed over its replicas."""
+    cfg = wl.scaled(wl.CONFIGS["cfg5_train"], name="cfg5_placed", T=1024, d=128, f=256, E=16, K=2, G=8,
+                    bias_kind="scaled_z", bias_scale=1.5)
+    inp = wl.make_inputs(cfg, DEV)
+    place = wl.placement_z2xz4()                        # Appendix B Example 3: 16 experts on 8 ranks, two replicas each
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+    layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+    layer.forward(place=torch.from_numpy(place).to(DEV))
+    bwd = GpuBackward(layer)
+    bwd.run()
+    idx = layer.topk_idx.cpu().numpy()
+    want = check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G, place)
+    seg = want["seg_off"]
+    assert ((np.diff(seg, axis=1) > 0).sum(axis=0) == 2).any()       # some expert really runs on both of its ranks
+    g = moe.backward_dense(to64(inp.x), idx, to64(layer.topk_w), weights_of_factory(inp), to64(inp.d_out))
+    assert max_rel_err(to64(bwd.d_x), g["d_x"]) <= TOL
+    assert max_rel_err(to64(bwd.d_topk_w), g["d_topk_w"]) <= TOL
+    for e in range(cfg.E):
+        for got, key in ((bwd.d_wg, "d_w_gate"), (bwd.d_wu, "d_w_up"), (bwd.d_wd, "d_w_down")):
+            if e in g[key]:
+                assert max_rel_err(to64(got[e]), g[key][e]) <= TOL, (key, e)
+            else:
+                assert not got[e].any(), (key, e)
+
+
 def test_backward_full_size_cfg5_sampled():
     cfg = wl.CONFIGS["cfg5_train"]
     print("full-size backward cfg5", flush=True)
