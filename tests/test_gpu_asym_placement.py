@@ -76,6 +76,10 @@ SEARCH_CASES = [
     ("flow_cfg4_like_g32", 256, 32, 10, "1.0", 32768, 4, 13),
     ("flow_g32_tight", 64, 32, 2, "1.3", 32768, 6, 14),
     ("flow_g64", 64, 64, 2, "1.1", 10000, 3, 15),
+    # the largest tables that fit: 1024 experts next to the 2^13-entry subset table; 512 experts x 24 ranks of flow tables
+    ("e1024_g16", 1024, 16, 80, "1.1", 100000, 2, 16),
+    ("e1024_g8", 1024, 8, 160, "0.9", 50000, 3, 17),
+    ("flow_e512_g24", 512, 24, 30, "1.2", 60000, 2, 18),
 ]
 
 
