@@ -59,6 +59,11 @@ def parse():
                          "fine_replica_counts + fine_place_search from the loads of the workload's own gate")
     ap.add_argument("--placement-search", action="store_true",
                     help="time the placement construction from the workload's expert loads instead of the layer")
+    ap.add_argument("--stream", type=int, default=0, metavar="N",
+                    help="time a stream of N micro-batches whose gate bias drifts (Section 4.1 warm start, Section "
+                         "4.4 overlap): forward path under a searched placement, scheduling cold / warm / on a second "
+                         "stream; prints the scheduling time left exposed per micro-batch")
+    ap.add_argument("--drift", type=float, default=0.05, help="std of the bias random walk per micro-batch (--stream)")
     ap.add_argument("--candidates", type=int, default=4096)
     ap.add_argument("--slots", type=int, default=0, help="replica slots per rank (default: 5 E / (4 G), rounded up)")
     return ap.parse_args()
@@ -91,6 +96,9 @@ def main():
         return
     if args.placement_search:
         run_placement_search(args, cfg, dev)
+        return
+    if args.stream:
+        run_stream(args, cfg, dev)
         return
     t_gen = time.time()
     inp = wl.make_inputs(cfg, dev)
@@ -425,6 +433,157 @@ def run_placement_search(args, cfg, dev):
         line["cpu_baseline"] = {"value": round(sample / dt, 2), "unit": "candidates/s", "cores": 1, "kind": "oracle",
                                 "sample": "the first %d of %d candidates drawn and scored by the oracle in %.1f s, each "
                                           "checked against the device's score" % (sample, n, dt)}
+    print(json.dumps(line))
+
+
+def run_stream(args, cfg, dev):
+    """N micro-batches through the forward path (gate, scheduling, permute, expert FFN per rank, combine)
+    under one restricted placement built from the first micro-batch's loads.  The gate bias takes a
+    random-walk step per micro-batch, so the loads move while the placement stays (Section 4.1).  Timed
+    four ways: without any scheduling (schedules precomputed: the floor), scheduling in line cold, in
+    line warm-started from the previous micro-batch's replica loads, and warm on a second stream while
+    the previous micro-batch computes (Section 4.4 overlaps scheduling with work that does not need its
+    result; here that work is the neighbouring micro-batch's expert computation)."""
+    import numpy as np
+    import torch
+
+    import paper_2511_16947_amd as fm
+    import workloads as wl
+
+    n = args.stream
+    inp = wl.make_inputs(cfg, dev)
+    s = fm.shape_of(cfg, fm.FLAG_LOCALITY | (args.tile << 8))
+    gen = torch.Generator(device="cpu").manual_seed(1234 + cfg.seed)
+    walk = torch.cumsum(args.drift * torch.randn(n, cfg.E, generator=gen), dim=0)
+    walk[0] = 0.0
+    biases = [(inp.bias + walk[i].to(dev)).contiguous() for i in range(n)]
+    topk_idx = [torch.empty(s.T, s.K, dtype=torch.int32, device=dev) for _ in range(2)]
+    topk_w = [torch.empty(s.T, s.K, dtype=torch.float32, device=dev) for _ in range(2)]
+    sbs = [fm.SchedBuffers(s, dev) for _ in range(2)]
+    x_perm = torch.empty(s.P, s.d, dtype=s.torch_dtype, device=dev)
+    y_perm = torch.empty(s.P, s.d, dtype=s.torch_dtype, device=dev)
+    out = torch.empty(s.T, s.d, dtype=s.torch_dtype, device=dev)
+    ws_ffn = fm.alloc_workspace(s, fm.WS_FFN, dev)
+
+    # placement from the first micro-batch's loads (Section 5.3)
+    slots = args.slots or -(-5 * s.E // (4 * s.G))
+    fm.fine_topk(s, inp.x, inp.w_router, biases[0], topk_idx[0], topk_w[0])
+    sbs[0].run(s, topk_idx[0], None)
+    counts = torch.empty(s.E, dtype=torch.int32, device=dev)
+    m_num = torch.empty(args.candidates, dtype=torch.int64, device=dev)
+    m_den = torch.empty(args.candidates, dtype=torch.int32, device=dev)
+    best = torch.empty(1, dtype=torch.int32, device=dev)
+    place = torch.empty(s.E, s.G, dtype=torch.uint8, device=dev)
+    fm.fine_replica_counts(s, sbs[0].load, slots, counts)
+    fm.fine_place_search(s, sbs[0].load, counts, slots, args.candidates, 0, m_num, m_den, best, place)
+    torch.cuda.synchronize()
+
+    def gate_and_schedule(i, warm):
+        b, sb = i & 1, sbs[i & 1]
+        fm.fine_topk(s, inp.x, inp.w_router, biases[i], topk_idx[b], topk_w[b])
+        fm.fine_sched_warm(s, topk_idx[b], place, sbs[b ^ 1].x_eg if warm and i > 0 else None, sb.load, sb.input_eg,
+                           sb.x_eg, sb.max_load, sb.pair_dst, sb.row_of_pair, sb.pair_of_row, sb.seg_off, sb.rank_off,
+                           sb.ws)
+
+    def compute(i):
+        b, sb = i & 1, sbs[i & 1]
+        fm.fine_permute(s, inp.x, sb.pair_of_row, x_perm)
+        for r in range(s.G):
+            fm.fine_grouped_ffn(s, r, x_perm, inp.w_gate, inp.w_up, inp.w_down, sb.seg_off, y_perm, None, ws_ffn)
+        fm.fine_combine(s, y_perm, sb.row_of_pair, topk_w[b], out)
+
+    def in_line(warm):
+        for i in range(n):
+            gate_and_schedule(i, warm)
+            compute(i)
+
+    # the floor: every micro-batch's schedule kept from a pass made beforehand
+    kept = []
+    for i in range(n):
+        gate_and_schedule(i, False)
+        sb = sbs[i & 1]
+        kept.append((sb.pair_of_row.clone(), sb.seg_off.clone(), sb.row_of_pair.clone(), topk_w[i & 1].clone(),
+                     int(sb.max_load.cpu()[0]), sb.x_eg.clone()))
+
+    def no_scheduling():
+        for i in range(n):
+            por, seg, rop, tw, _, _ = kept[i]
+            fm.fine_permute(s, inp.x, por, x_perm)
+            for r in range(s.G):
+                fm.fine_grouped_ffn(s, r, x_perm, inp.w_gate, inp.w_up, inp.w_down, seg, y_perm, None, ws_ffn)
+            fm.fine_combine(s, y_perm, rop, tw, out)
+
+    main_stream = torch.cuda.current_stream()
+    side = torch.cuda.Stream()                     # default priority
+    scheduled = [torch.cuda.Event() for _ in range(n)]
+    computed = [torch.cuda.Event() for _ in range(n)]
+
+    def second_stream():
+        """Micro-batch i+1 is gated and scheduled on `side` while micro-batch i computes on the main
+        stream; buffer set (i+1)&1 is free once micro-batch i-1 has been combined."""
+        side.wait_stream(main_stream)
+        with torch.cuda.stream(side):
+            gate_and_schedule(0, True)
+            scheduled[0].record(side)
+        for i in range(n):
+            if i + 1 < n:
+                with torch.cuda.stream(side):
+                    if i >= 1:
+                        side.wait_event(computed[i - 1])
+                    gate_and_schedule(i + 1, True)
+                    scheduled[i + 1].record(side)
+            main_stream.wait_event(scheduled[i])
+            compute(i)
+            computed[i].record(main_stream)
+        main_stream.wait_stream(side)
+
+    def timed(fn):
+        for _ in range(max(1, args.warmup // 10)):
+            fn()
+        torch.cuda.synchronize()
+        reps = max(1, args.steps // 10)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps / n
+
+    # the schedules of the overlapped run are the in-line ones (same kernels, same inputs)
+    second_stream()
+    torch.cuda.synchronize()
+    last = sbs[(n - 1) & 1]
+    assert torch.equal(last.x_eg, kept[n - 1][5]) and torch.equal(last.pair_of_row, kept[n - 1][0])
+
+    ms = {"no_scheduling": timed(no_scheduling), "in_line_cold": timed(lambda: in_line(False)),
+          "in_line_warm": timed(lambda: in_line(True)), "second_stream_warm": timed(second_stream)}
+    # gate + scheduling alone, per micro-batch (events on the launch stream)
+    alone = {}
+    for name, warm in (("cold", False), ("warm", True)):
+        evs = []
+        for _ in range(3):
+            for i in range(n):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record(); gate_and_schedule(i, warm); b.record()
+                evs.append((a, b))
+        torch.cuda.synchronize()
+        alone[name] = float(np.mean([a.elapsed_time(b) for a, b in evs[n:]]))
+    exposed = {k: round((v - ms["no_scheduling"]) * 1e3, 1) for k, v in ms.items() if k != "no_scheduling"}
+    flop = 6.0 * s.P * s.d * s.f
+    line = {
+        "metric": "gate + scheduling time left exposed per micro-batch (Sections 4.1, 4.4)",
+        "value": exposed["second_stream_warm"], "unit": "us", "n_gpus": 1, "steps": max(1, args.steps // 10) * n,
+        "warmup": max(1, args.warmup // 10) * n, "ms_per_step": round(ms["second_stream_warm"], 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "%s_stream" % cfg.name, "micro_batches": n, "bias_drift": args.drift,
+                   "placement": "%d replica slots per rank, best of %d candidates on the first micro-batch's loads"
+                                % (slots, args.candidates),
+                   "launch": "forward path, one FFN call per rank; a step = one micro-batch"},
+        "roofline": None, "cpu_baseline": None,
+        "detail": {"ms_per_micro_batch": {k: round(v, 4) for k, v in ms.items()}, "exposed_us": exposed,
+                   "gate_and_scheduling_alone_us": {k: round(v * 1e3, 1) for k, v in alone.items()},
+                   "tflops_second_stream": round(flop / (ms["second_stream_warm"] * 1e-3) / 1e12, 1),
+                   "max_load_per_micro_batch": [k[4] for k in kept], "perfect": -(-s.P // s.G)},
+    }
     print(json.dumps(line))
 
 

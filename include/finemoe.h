@@ -120,6 +120,25 @@ int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* 
                void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Token scheduling of the next micro-batch of a stream (Section 4.1: across micro-batches the
+ * placement stays and only the loads change, so the solver starts from the previous solution).
+ * Same arguments and the same results, bit for bit, as fine_sched, plus
+ *   x_prev [E,G] int32 (device) or NULL: replica loads of an earlier micro-batch, normally the
+ *          x_eg that the last call wrote.  It only sets where the search for the optimum
+ *          starts: each expert's row, restricted to its replicas in `place`, is scaled to the
+ *          new load_e.  Any content is allowed (negative entries read as 0; rows of another
+ *          placement or of zeros fall back to the cold start for that expert).  May be the
+ *          same buffer as x_eg: it is read completely before x_eg is written.
+ * NULL, or place == NULL (closed form, nothing to search), makes this fine_sched.
+ */
+int fine_sched_warm(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
+                    const int32_t* x_prev,
+                    int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
+                    int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+                    int32_t* seg_off, int32_t* rank_off,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Permutation (Section 4.4: replicate tokens by top-K and sort them before dispatch).
  * x_perm[row] = x[pair_of_row[row] / K].   x [T,d] dtype -> x_perm [P,d] dtype.
  */

@@ -30,6 +30,7 @@ FLAG_LOCALITY, FLAG_SIMPLE_FFN, FLAG_ONLY_GEMM1, FLAG_ONLY_GEMM2 = 1, 2, 4, 8
 WS_TOPK, WS_SCHED, WS_FFN, WS_BACKWARD = 0, 1, 2, 3
 
 EXPORTS = ["fine_version", "fine_last_hip_error", "fine_workspace_bytes", "fine_topk", "fine_sched",
+           "fine_sched_warm",
            "fine_permute", "fine_grouped_ffn", "fine_combine", "fine_backward", "fine_replica_counts",
            "fine_eval_placements", "fine_place_search"]
 
@@ -70,6 +71,8 @@ def load_library() -> ctypes.CDLL:
     lib.fine_topk.argtypes = [sp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fine_sched.restype = ctypes.c_int
     lib.fine_sched.argtypes = [sp] + [vp] * 11 + [vp, sz, vp]
+    lib.fine_sched_warm.restype = ctypes.c_int
+    lib.fine_sched_warm.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
     lib.fine_permute.restype = ctypes.c_int
     lib.fine_permute.argtypes = [sp, vp, vp, vp, vp]
     lib.fine_grouped_ffn.restype = ctypes.c_int
@@ -159,6 +162,15 @@ def fine_sched(shape: Shape, topk_idx, place, load, input_eg, x_eg, max_load, pa
     _check("fine_sched", rc)
 
 
+def fine_sched_warm(shape: Shape, topk_idx, place, x_prev, load, input_eg, x_eg, max_load, pair_dst, row_of_pair,
+                    pair_of_row, seg_off, rank_off, ws):
+    cs = shape.c()
+    rc = load_library().fine_sched_warm(ctypes.byref(cs), _ptr(topk_idx), _ptr(place), _ptr(x_prev), _ptr(load),
+                                        _ptr(input_eg), _ptr(x_eg), _ptr(max_load), _ptr(pair_dst), _ptr(row_of_pair),
+                                        _ptr(pair_of_row), _ptr(seg_off), _ptr(rank_off), _ptr(ws), ws.numel(), _stream())
+    _check("fine_sched_warm", rc)
+
+
 def fine_permute(shape: Shape, x, pair_of_row, x_perm):
     cs = shape.c()
     _check("fine_permute", load_library().fine_permute(ctypes.byref(cs), _ptr(x), _ptr(pair_of_row), _ptr(x_perm), _stream()))
@@ -227,8 +239,9 @@ class SchedBuffers:
         self.rank_off = torch.empty(G + 1, **i32)
         self.ws = alloc_workspace(shape, WS_SCHED, device)
 
-    def run(self, shape: Shape, topk_idx, place=None):
-        fine_sched(shape, topk_idx, place, self.load, self.input_eg, self.x_eg, self.max_load, self.pair_dst,
+    def run(self, shape: Shape, topk_idx, place=None, warm: bool = False):
+        """warm: start from the replica loads this object holds from its last run."""
+        fine_sched_warm(shape, topk_idx, place, self.x_eg if warm else None, self.load, self.input_eg, self.x_eg, self.max_load, self.pair_dst,
                    self.row_of_pair, self.pair_of_row, self.seg_off, self.rank_off, self.ws)
 
 

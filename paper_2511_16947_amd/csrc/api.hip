@@ -78,10 +78,10 @@ int fine_topk(const fine_shape* shape, const void* x, const void* w_router, cons
     return launch_topk(*shape, x, w_router, bias, topk_idx, topk_w, (hipStream_t)stream);
 }
 
-int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
-               int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
-               int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
-               int32_t* seg_off, int32_t* rank_off, void* ws, size_t ws_bytes, void* stream) {
+int fine_sched_warm(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place, const int32_t* x_prev,
+                    int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
+                    int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+                    int32_t* seg_off, int32_t* rank_off, void* ws, size_t ws_bytes, void* stream) {
     FINE_TRY(check_shape(shape));
     if (!topk_idx || !load || !input_eg || !x_eg || !max_load || !pair_dst || !row_of_pair || !pair_of_row ||
         !seg_off || !rank_off || !ws)
@@ -89,8 +89,16 @@ int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* 
     if (!aligned16(ws)) return FINE_INVALID_ARG;
     if (ws_bytes < sched_ws_layout(*shape).total) return FINE_WORKSPACE_TOO_SMALL;
     if (shape->T == 0) return FINE_INVALID_ARG;
-    return launch_sched(*shape, topk_idx, place, load, input_eg, x_eg, max_load, pair_dst, row_of_pair,
+    return launch_sched(*shape, topk_idx, place, x_prev, load, input_eg, x_eg, max_load, pair_dst, row_of_pair,
                         pair_of_row, seg_off, rank_off, (char*)ws, (hipStream_t)stream);
+}
+
+int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
+               int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
+               int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+               int32_t* seg_off, int32_t* rank_off, void* ws, size_t ws_bytes, void* stream) {
+    return fine_sched_warm(shape, topk_idx, place, nullptr, load, input_eg, x_eg, max_load, pair_dst, row_of_pair,
+                           pair_of_row, seg_off, rank_off, ws, ws_bytes, stream);
 }
 
 int fine_permute(const fine_shape* shape, const void* x, const int32_t* pair_of_row, void* x_perm, void* stream) {

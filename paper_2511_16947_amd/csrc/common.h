@@ -121,7 +121,7 @@ BwdWs bwd_ws_layout(const fine_shape& s);
 int launch_topk(const fine_shape& s, const void* x, const void* w_router, const float* bias,
                 int32_t* topk_idx, float* topk_w, hipStream_t st);
 
-int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place,
+int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place, const int32_t* x_prev,
                  int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
                  int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
                  int32_t* seg_off, int32_t* rank_off, char* ws, hipStream_t st);

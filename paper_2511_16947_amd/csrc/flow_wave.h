@@ -24,24 +24,24 @@ struct Ctx {
 
 __device__ inline int lane() { return threadIdx.x; }
 
-__device__ inline int wave_sum_i(int v) {
-#pragma unroll
-    for (int off = kW / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kW);
-    return v;
-}
-__device__ inline int wave_min_i(int v) {
-#pragma unroll
-    for (int off = kW / 2; off > 0; off >>= 1) v = min(v, __shfl_xor(v, off, kW));
-    return v;
+// Wave-wide scan and sum by DPP (data-parallel primitives: an operand taken from another lane of
+// the same ALU instruction), six steps and no LDS traffic: shifts by 1, 2, 4, 8 inside each row of
+// 16 lanes, then lane 15 of rows 0 and 2 added to rows 1 and 3, then lane 31 to rows 2 and 3.  A lane
+// whose source lies outside its row takes the first argument (0).  All 64 lanes must be active.
+template <int CTRL, int ROW_MASK>
+__device__ inline int dpp_from(int identity, int v) {
+    return __builtin_amdgcn_update_dpp(identity, v, CTRL, ROW_MASK, 0xf, false);
 }
 __device__ inline int wave_incl_scan_i(int v) {
-#pragma unroll
-    for (int off = 1; off < kW; off <<= 1) {
-        int o = __shfl_up(v, off, kW);
-        if (lane() >= off) v += o;
-    }
+    v += dpp_from<0x111, 0xf>(0, v);     // row_shr:1
+    v += dpp_from<0x112, 0xf>(0, v);     // row_shr:2
+    v += dpp_from<0x114, 0xf>(0, v);     // row_shr:4
+    v += dpp_from<0x118, 0xf>(0, v);     // row_shr:8
+    v += dpp_from<0x142, 0xa>(0, v);     // row_bcast:15 into rows 1 and 3
+    v += dpp_from<0x143, 0xc>(0, v);     // row_bcast:31 into rows 2 and 3
     return v;
 }
+__device__ inline int wave_sum_i(int v) { return __builtin_amdgcn_readlane(wave_incl_scan_i(v), kW - 1); }
 
 // replicas of expert e whose variables are still free when variable (e_cur, g_cur) is being set
 __device__ inline u64 free_mask(const Ctx& c, int e, int e_cur, int g_cur) {
@@ -72,7 +72,7 @@ __device__ inline void move_units(const Ctx& c, int a, int b, int amount, int e_
             while (Fa) { int q = __ffsll((long long)Fa) - 1; Fa &= Fa - 1; atomicAdd(&c.A[a * c.AS + q], -t); }
             while (Fb) { int q = __ffsll((long long)Fb) - 1; Fb &= Fb - 1; atomicAdd(&c.A[b * c.AS + q], t); }
         }
-        remaining -= min(remaining, __shfl(inc, kW - 1, kW));
+        remaining -= min(remaining, __builtin_amdgcn_readlane(inc, kW - 1));
         __syncthreads();
     }
     if (lane() == 0) { c.ld[a] -= amount; c.ld[b] += amount; }
@@ -87,9 +87,16 @@ __device__ inline void move_units(const Ctx& c, int a, int b, int amount, int e_
 __device__ inline int bfs(const Ctx& c, int src, bool want, u64* visited_out, int* len_out, int* cap_out) {
     const int b = lane();
     u64 inmask = 0ull;
-    if (b < c.G)
-        for (int a = 0; a < c.G; ++a)
-            if (c.A[a * c.AS + b] > 0) inmask |= 1ull << a;
+    if (b < c.G) {
+        for (int a0 = 0; a0 < c.G; a0 += 8) {         // eight independent LDS reads in flight
+            int v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (a0 + j < c.G) ? c.A[(a0 + j) * c.AS + b] : 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (v[j] > 0) inmask |= 1ull << (a0 + j);
+        }
+    }
     u64 visited = 1ull << src, frontier = visited;
     int parent = -1, target = -1;
     while (true) {
@@ -107,7 +114,7 @@ __device__ inline int bfs(const Ctx& c, int src, bool want, u64* visited_out, in
     if (target < 0) return -1;
     int len = 0, cap = 0x7fffffff, cur = target;
     while (cur != src) {
-        const int p = __shfl(parent, cur, kW);
+        const int p = __builtin_amdgcn_readlane(parent, __builtin_amdgcn_readfirstlane(cur));   // cur is wave-uniform
         if (lane() == 0) { c.path[2 * len] = p; c.path[2 * len + 1] = cur; }
         cap = min(cap, c.A[p * c.AS + cur]);
         cur = p;

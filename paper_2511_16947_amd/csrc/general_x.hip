@@ -52,8 +52,55 @@ __device__ void pull_expert(const Ctx& c, int e, int g, u64 later, u64 from, int
     __syncthreads();
 }
 
+// Warm start (Section 4.1: between micro-batches only the loads change, so the previous solution is
+// a good place to start from).  Every expert's previous row, restricted to its replicas, is scaled
+// to the new load (rounded down, the remainder to the first replica); x, A and the rank loads are
+// filled from that.  Any assignment of the loads to replicas is a valid start for phase 1, and the
+// result of phase 2 does not depend on where it started, so `prev` may hold anything: negative
+// entries read as 0, a row without units falls back to the first replica.  Same contract as
+// start_on_first_replicas.  `prev` is read completely before the barrier that ends this function.
+__device__ bool start_from_previous(const Ctx& c, const int32_t* __restrict__ load, const int32_t* prev) {
+    const int l = lane();
+    for (int i = l; i < c.G * c.AS; i += kW) c.A[i] = 0;
+    for (int i = l; i < c.G; i += kW) c.ld[i] = 0;
+    for (int i = l; i < c.E * c.G; i += kW) c.x[i] = 0;
+    __syncthreads();
+    int bad = 0;
+    for (int e = l; e < c.E; e += kW) {
+        const u64 m = c.pm[e];
+        const long long le = max(load[e], 0);
+        if (m == 0ull) {
+            if (le > 0) bad = 1;
+            continue;
+        }
+        if (le == 0) continue;
+        const int first = __ffsll((long long)m) - 1;
+        long long had = 0;
+        for (u64 r = m; r; r &= r - 1) had += max(prev[(size_t)e * c.G + (__ffsll((long long)r) - 1)], 0);
+        long long given = 0;
+        if (had > 0) {
+            for (u64 r = m; r; r &= r - 1) {
+                const int g = __ffsll((long long)r) - 1;
+                const long long t = (long long)max(prev[(size_t)e * c.G + g], 0) * le / had;
+                c.x[e * c.G + g] = (int)t;
+                given += t;
+            }
+        }
+        c.x[e * c.G + first] += (int)(le - given);
+        for (u64 r = m; r; r &= r - 1) {
+            const int a = __ffsll((long long)r) - 1;
+            const int t = c.x[e * c.G + a];
+            if (t == 0) continue;
+            atomicAdd(&c.ld[a], t);
+            for (u64 o = m & ~(1ull << a); o; o &= o - 1) atomicAdd(&c.A[a * c.AS + (__ffsll((long long)o) - 1)], t);
+        }
+    }
+    __syncthreads();
+    return __ballot(bad) != 0ull;
+}
+
 __global__ __launch_bounds__(64) void k_general_x(const uint8_t* __restrict__ place, const int32_t* __restrict__ load,
-                                                  int E, int G, int P, int32_t* __restrict__ x_out,
+                                                  const int32_t* prev, int E, int G, int P, int32_t* x_out,
                                                   int32_t* __restrict__ max_load) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     Ctx c = make_ctx(smem, E, G);
@@ -67,7 +114,8 @@ __global__ __launch_bounds__(64) void k_general_x(const uint8_t* __restrict__ pl
         c.pm[e] = m;
     }
     __syncthreads();
-    if (start_on_first_replicas(c, load)) {        // an expert with load and no replica: no schedule exists
+    const bool stuck = prev ? start_from_previous(c, load, prev) : start_on_first_replicas(c, load);
+    if (stuck) {                                   // an expert with load and no replica: no schedule exists
         for (int i = l; i < E * G; i += kW) x_out[i] = 0;
         if (l == 0) max_load[0] = -1;
         return;
@@ -130,9 +178,8 @@ __global__ __launch_bounds__(64) void k_general_x(const uint8_t* __restrict__ pl
 
 }  // namespace
 
-int launch_general_x(const fine_shape& s, const uint8_t* place, const int32_t* load, int32_t* x_eg,
-                     int32_t* max_load, int32_t* scratch, hipStream_t st) {
-    (void)scratch;
+int launch_general_x(const fine_shape& s, const uint8_t* place, const int32_t* load, const int32_t* x_prev,
+                     int32_t* x_eg, int32_t* max_load, hipStream_t st) {
     const size_t lds = flow::ctx_bytes(s.E, s.G);
     if (lds > 160 * 1024) return FINE_UNSUPPORTED;
     static bool attr_done = false;
@@ -141,7 +188,7 @@ int launch_general_x(const fine_shape& s, const uint8_t* place, const int32_t* l
                                                160 * 1024)));
         attr_done = true;
     }
-    hipLaunchKernelGGL(k_general_x, dim3(1), dim3(64), lds, st, place, load, s.E, s.G, s.T * s.K, x_eg, max_load);
+    hipLaunchKernelGGL(k_general_x, dim3(1), dim3(64), lds, st, place, load, x_prev, s.E, s.G, s.T * s.K, x_eg, max_load);
     FINE_LAUNCH_CHECK();
     return FINE_OK;
 }

@@ -234,10 +234,10 @@ SchedWs sched_ws_layout(const fine_shape& s) {
     return w;
 }
 
-int launch_general_x(const fine_shape& s, const uint8_t* place, const int32_t* load, int32_t* x_eg,
-                     int32_t* max_load, int32_t* scratch, hipStream_t st);
+int launch_general_x(const fine_shape& s, const uint8_t* place, const int32_t* load, const int32_t* x_prev,
+                     int32_t* x_eg, int32_t* max_load, hipStream_t st);
 
-int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place,
+int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place, const int32_t* x_prev,
                  int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
                  int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
                  int32_t* seg_off, int32_t* rank_off, char* ws, hipStream_t st) {
@@ -261,7 +261,7 @@ int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* pl
                            load, input_eg, s.E, s.G, P, locality, x_eg, max_load, Y, Ypre);
         FINE_LAUNCH_CHECK();
     } else {
-        FINE_TRY(launch_general_x(s, place, load, x_eg, max_load, reinterpret_cast<int32_t*>(ws + L.solver), st));
+        FINE_TRY(launch_general_x(s, place, load, x_prev, x_eg, max_load, st));
         hipLaunchKernelGGL(k_tables<false>, dim3(s.E), dim3(64), 0, st,
                            load, input_eg, s.E, s.G, P, locality, x_eg, max_load, Y, Ypre);
         FINE_LAUNCH_CHECK();

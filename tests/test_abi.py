@@ -52,6 +52,12 @@ def test_null_pointers_are_rejected_without_touching_the_gpu(lib):
     assert rc == fm.FINE_INVALID_ARG
     bad = fm.Shape(256, 128, 256, 8, 9, 4, fm.FINE_F32).c()
     assert lib.fine_permute(ctypes.byref(bad), None, None, None, None) == fm.FINE_INVALID_ARG
+    # both scheduling entry points: outputs and workspace are required, x_prev is optional
+    none12 = [None] * 12
+    assert lib.fine_sched_warm(ctypes.byref(s), *none12, None, 0, None) == fm.FINE_INVALID_ARG
+    assert lib.fine_sched(ctypes.byref(s), *none12[:11], None, 0, None) == fm.FINE_INVALID_ARG
+    buf = ctypes.c_void_p(4096)        # non-null, 16-byte aligned; the size check below fails before any use
+    assert lib.fine_sched_warm(ctypes.byref(s), buf, None, None, *([buf] * 9), buf, 16, None) == fm.FINE_WORKSPACE_TOO_SMALL
     # the placement entry points check their arguments on the host as well
     assert lib.fine_replica_counts(ctypes.byref(s), None, 4, None, None) == fm.FINE_INVALID_ARG
     assert lib.fine_eval_placements(ctypes.byref(s), 1, None, None, None, None, None) == fm.FINE_INVALID_ARG

@@ -156,6 +156,20 @@ def random_topk(T: int, E: int, K: int, seed: int, skew: float = 0.0) -> np.ndar
     return out
 
 
+def drifting_topk_stream(T: int, E: int, K: int, n: int, seed: int, skew: float = 1.0, drift: float = 0.05):
+    """Routing tables of n consecutive micro-batches (Section 4.1: the placement
+    stays, the loads move a little from one micro-batch to the next).  Token t of
+    micro-batch i picks the K largest of bias_i[e] + Gumbel noise; bias_0 is
+    skew * log of a seeded Zipf(1) profile and bias_{i+1} = bias_i + drift * N(0,1).
+    Yields int32 arrays [T,K] with distinct experts per token."""
+    rng = np.random.default_rng(seed)
+    bias = -skew * np.log(rng.permutation(E) + 1.0)
+    for _ in range(n):
+        scores = bias[None, :] + rng.gumbel(size=(T, E))
+        yield np.argsort(-scores, axis=1, kind="stable")[:, :K].astype(np.int32)
+        bias = bias + drift * rng.standard_normal(E)
+
+
 def zipf_loads(E: int, total: int, s: float, seed: int) -> np.ndarray:
     """Integer expert loads summing to `total`, the i-th most loaded expert
     proportional to i^(-s); which expert is the i-th is a seeded permutation."""
