@@ -50,32 +50,49 @@ __device__ inline u64 free_mask(const Ctx& c, int e, int e_cur, int g_cur) {
     return 0ull;
 }
 
-// Move `amount` units of free load from rank a to rank b (experts in ascending order).
+__device__ inline u64 readlane_u64(u64 v, int src) {
+    const unsigned lo = __builtin_amdgcn_readlane((int)(unsigned)v, src), hi = __builtin_amdgcn_readlane((int)(unsigned)(v >> 32), src);
+    return ((u64)hi << 32) | lo;
+}
+
+// Move `amount` units of free load from rank a to rank b (experts in ascending order; e_cur < 0:
+// every variable is free).  A lane past the last expert reads the last expert's entries (in bounds,
+// no branch, so the two LDS reads go out together) and takes no part.  The experts that give units
+// are then taken one by one, lane q = rank q updating its own entries of rows a and b of A: two
+// LDS updates per giving expert whatever its number of replicas.
 __device__ inline void move_units(const Ctx& c, int a, int b, int amount, int e_cur, int g_cur) {
     int remaining = amount;
+    const int q = lane();
     for (int base = (e_cur < 0 ? 0 : e_cur); base < c.E && remaining > 0; base += kW) {
-        const int e = base + lane();
-        u64 F = 0ull;
-        int m = 0;
-        if (e < c.E) {
-            F = free_mask(c, e, e_cur, g_cur);
-            if (((F >> a) & 1ull) && ((F >> b) & 1ull)) m = c.x[e * c.G + a];
-        }
+        const int e = base + q;                       // >= e_cur: earlier experts are never looked at
+        const bool in = e < c.E;
+        const int ee = in ? e : c.E - 1;
+        const u64 pm = c.pm[ee];
+        const int xa = c.x[ee * c.G + a];
+        const u64 F = (e == e_cur) ? (pm & ~((2ull << g_cur) - 1ull)) : pm;
+        const int m = (in && ((F >> a) & 1ull) && ((F >> b) & 1ull)) ? xa : 0;
         if (__ballot(m > 0) == 0ull) continue;        // no expert of this chunk links a to b (wave-uniform)
         const int inc = wave_incl_scan_i(m);
-        const int before = inc - m;
-        const int t = max(0, min(m, remaining - before));
+        const int t = max(0, min(m, remaining - (inc - m)));
         if (t > 0) {
-            c.x[e * c.G + a] -= t;
+            c.x[e * c.G + a] = xa - t;
             c.x[e * c.G + b] += t;
-            u64 Fa = F & ~(1ull << a), Fb = F & ~(1ull << b);
-            while (Fa) { int q = __ffsll((long long)Fa) - 1; Fa &= Fa - 1; atomicAdd(&c.A[a * c.AS + q], -t); }
-            while (Fb) { int q = __ffsll((long long)Fb) - 1; Fb &= Fb - 1; atomicAdd(&c.A[b * c.AS + q], t); }
+        }
+        u64 givers = __ballot(t > 0);
+        while (givers) {
+            const int src = __ffsll((long long)givers) - 1;
+            givers &= givers - 1;
+            const int ts = __builtin_amdgcn_readlane(t, src);
+            const u64 Fs = readlane_u64(F, src);
+            if (q < c.G && ((Fs >> q) & 1ull)) {
+                if (q != a) c.A[a * c.AS + q] -= ts;
+                if (q != b) c.A[b * c.AS + q] += ts;
+            }
         }
         remaining -= min(remaining, __builtin_amdgcn_readlane(inc, kW - 1));
         __syncthreads();
     }
-    if (lane() == 0) { c.ld[a] -= amount; c.ld[b] += amount; }
+    if (q == 0) { c.ld[a] -= amount; c.ld[b] += amount; }
     __syncthreads();
 }
 
@@ -88,13 +105,14 @@ __device__ inline int bfs(const Ctx& c, int src, bool want, u64* visited_out, in
     const int b = lane();
     u64 inmask = 0ull;
     if (b < c.G) {
-        for (int a0 = 0; a0 < c.G; a0 += 8) {         // eight independent LDS reads in flight
+        // eight independent LDS reads in flight; no branch between them (a row index past the end
+        // reads the last row again and is masked out), so that one wait covers all eight
+        for (int a0 = 0; a0 < c.G; a0 += 8) {
             int v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = (a0 + j < c.G) ? c.A[(a0 + j) * c.AS + b] : 0;
+            for (int j = 0; j < 8; ++j) v[j] = c.A[min(a0 + j, c.G - 1) * c.AS + b];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (v[j] > 0) inmask |= 1ull << (a0 + j);
+            for (int j = 0; j < 8; ++j) inmask |= (u64)((v[j] > 0) & (a0 + j < c.G)) << (a0 + j);
         }
     }
     u64 visited = 1ull << src, frontier = visited;

@@ -36,15 +36,22 @@ __device__ void pull_expert(const Ctx& c, int e, int g, u64 later, u64 from, int
     const int q = lane();
     const bool src = q < c.G && ((from >> q) & 1ull);
     const int m = src ? c.x[e * c.G + q] : 0;
-    const int before = wave_incl_scan_i(m) - m;
-    const int t = max(0, min(m, amount - before));
+    const int inc = wave_incl_scan_i(m);
+    const int t = max(0, min(m, amount - (inc - m)));
     if (t > 0) {
-        c.x[e * c.G + q] -= t;
+        c.x[e * c.G + q] = m - t;
         c.ld[q] -= t;
-        u64 others = later & ~(1ull << q);            // row q of A belongs to this lane alone
-        while (others) { int r = __ffsll((long long)others) - 1; others &= others - 1; c.A[q * c.AS + r] -= t; }
     }
-    const int total = wave_sum_i(t);
+    // row s of A loses what source s gave towards every other later replica: lane q = column q
+    u64 givers = __ballot(t > 0);
+    int total = 0;
+    while (givers) {
+        const int s = __ffsll((long long)givers) - 1;
+        givers &= givers - 1;
+        const int ts = __builtin_amdgcn_readlane(t, s);
+        total += ts;
+        if (q < c.G && q != s && ((later >> q) & 1ull)) c.A[s * c.AS + q] -= ts;
+    }
     if (q == 0) {                                      // g is not among the later replicas: nobody else writes these
         c.x[e * c.G + g] += total;
         c.ld[g] += total;
