@@ -16,10 +16,13 @@ typedef unsigned long long u64;
 struct Ctx {
     int* x;        // [E][G]
     u64* pm;       // [E] replica masks
-    int* A;        // [G][G+1]
+    int* A;        // [G][AS], stored by destination: a(from, to) = A[to * AS + from]; 16-byte aligned,
+                   // entries from >= G are padding and stay 0
     int* ld;       // [G]
     int* path;     // [2*G] edges (from, to)
-    int E, G, AS;  // AS = row stride of A
+    int E, G, AS;  // AS = row stride of A: a multiple of 4 that is an odd number of 16-byte pieces, so
+                   // that lanes reading 16 bytes of consecutive rows fall into different banks
+    __device__ int& a(int from, int to) const { return A[to * AS + from]; }
 };
 
 __device__ inline int lane() { return threadIdx.x; }
@@ -85,8 +88,8 @@ __device__ inline void move_units(const Ctx& c, int a, int b, int amount, int e_
             const int ts = __builtin_amdgcn_readlane(t, src);
             const u64 Fs = readlane_u64(F, src);
             if (q < c.G && ((Fs >> q) & 1ull)) {
-                if (q != a) c.A[a * c.AS + q] -= ts;
-                if (q != b) c.A[b * c.AS + q] += ts;
+                if (q != a) c.a(a, q) -= ts;
+                if (q != b) c.a(b, q) += ts;
             }
         }
         remaining -= min(remaining, __builtin_amdgcn_readlane(inc, kW - 1));
@@ -103,16 +106,22 @@ __device__ inline void move_units(const Ctx& c, int a, int b, int amount, int e_
 // capacity to *cap_out.
 __device__ inline int bfs(const Ctx& c, int src, bool want, u64* visited_out, int* len_out, int* cap_out) {
     const int b = lane();
+    // lane b's row of A holds what may move into b from every rank: 16-byte reads, four in flight,
+    // no branch between them (a piece index past the end reads the last piece again; its bits are
+    // dropped)
     u64 inmask = 0ull;
     if (b < c.G) {
-        // eight independent LDS reads in flight; no branch between them (a row index past the end
-        // reads the last row again and is masked out), so that one wait covers all eight
-        for (int a0 = 0; a0 < c.G; a0 += 8) {
-            int v[8];
+        const int4* row = reinterpret_cast<const int4*>(c.A + b * c.AS);
+        const int n4 = c.AS >> 2;
+        for (int i0 = 0; i0 < n4; i0 += 4) {
+            int4 v[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = c.A[min(a0 + j, c.G - 1) * c.AS + b];
+            for (int j = 0; j < 4; ++j) v[j] = row[min(i0 + j, n4 - 1)];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) inmask |= (u64)((v[j] > 0) & (a0 + j < c.G)) << (a0 + j);
+            for (int j = 0; j < 4; ++j) {
+                const unsigned bits = (v[j].x > 0) | ((v[j].y > 0) << 1) | ((v[j].z > 0) << 2) | ((v[j].w > 0) << 3);
+                inmask |= (u64)(i0 + j < n4 ? bits : 0u) << ((4 * (i0 + j)) & 63);      // a 17th piece is padding: no bits
+            }
         }
     }
     u64 visited = 1ull << src, frontier = visited;
@@ -134,7 +143,7 @@ __device__ inline int bfs(const Ctx& c, int src, bool want, u64* visited_out, in
     while (cur != src) {
         const int p = __builtin_amdgcn_readlane(parent, __builtin_amdgcn_readfirstlane(cur));   // cur is wave-uniform
         if (lane() == 0) { c.path[2 * len] = p; c.path[2 * len + 1] = cur; }
-        cap = min(cap, c.A[p * c.AS + cur]);
+        cap = min(cap, c.a(p, cur));
         cur = p;
         ++len;
     }
@@ -168,7 +177,7 @@ __device__ inline bool start_on_first_replicas(const Ctx& c, const int32_t* __re
             c.x[e * c.G + first] = le;
             atomicAdd(&c.ld[first], le);
             u64 others = m & ~(1ull << first);
-            while (others) { int q = __ffsll((long long)others) - 1; others &= others - 1; atomicAdd(&c.A[first * c.AS + q], le); }
+            while (others) { int q = __ffsll((long long)others) - 1; others &= others - 1; atomicAdd(&c.a(first, q), le); }
         }
     }
     __syncthreads();
@@ -204,16 +213,19 @@ __device__ inline int optimum_value(const Ctx& c, int P) {
 }
 
 // bytes of LDS behind a Ctx for E experts on G ranks
-__host__ __device__ inline size_t ctx_bytes(int E, int G) { return (size_t)E * 8 + ((size_t)E * G + (size_t)G * (G + 1) + 3 * G + 16) * 4; }
+__host__ __device__ inline int a_stride(int G) { const int q = ((G + 3) >> 2) | 1; return 4 * q; }
+__host__ __device__ inline size_t ctx_bytes(int E, int G) {
+    return (((size_t)E * 8 + 15) & ~(size_t)15) + ((size_t)G * a_stride(G) + (size_t)E * G + 3 * G + 16) * 4;
+}
 
-// the arrays of a Ctx laid out from `smem` (8-byte aligned)
+// the arrays of a Ctx laid out from `smem` (16-byte aligned)
 __device__ inline Ctx make_ctx(char* smem, int E, int G) {
     Ctx c;
-    c.E = E; c.G = G; c.AS = G + 1;
+    c.E = E; c.G = G; c.AS = a_stride(G);
     c.pm = reinterpret_cast<u64*>(smem);
-    c.x = reinterpret_cast<int*>(smem + (size_t)E * 8);
-    c.A = c.x + (size_t)E * G;
-    c.ld = c.A + (size_t)G * c.AS;
+    c.A = reinterpret_cast<int*>(smem + (((size_t)E * 8 + 15) & ~(size_t)15));
+    c.x = c.A + (size_t)G * c.AS;
+    c.ld = c.x + (size_t)E * G;
     c.path = c.ld + G;
     return c;
 }

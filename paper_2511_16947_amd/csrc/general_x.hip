@@ -50,7 +50,7 @@ __device__ void pull_expert(const Ctx& c, int e, int g, u64 later, u64 from, int
         givers &= givers - 1;
         const int ts = __builtin_amdgcn_readlane(t, s);
         total += ts;
-        if (q < c.G && q != s && ((later >> q) & 1ull)) c.A[s * c.AS + q] -= ts;
+        if (q < c.G && q != s && ((later >> q) & 1ull)) c.a(s, q) -= ts;
     }
     if (q == 0) {                                      // g is not among the later replicas: nobody else writes these
         c.x[e * c.G + g] += total;
@@ -99,7 +99,7 @@ __device__ bool start_from_previous(const Ctx& c, const int32_t* __restrict__ lo
             const int t = c.x[e * c.G + a];
             if (t == 0) continue;
             atomicAdd(&c.ld[a], t);
-            for (u64 o = m & ~(1ull << a); o; o &= o - 1) atomicAdd(&c.A[a * c.AS + (__ffsll((long long)o) - 1)], t);
+            for (u64 o = m & ~(1ull << a); o; o &= o - 1) atomicAdd(&c.a(a, (__ffsll((long long)o) - 1)), t);
         }
     }
     __syncthreads();
@@ -145,8 +145,8 @@ __global__ __launch_bounds__(64) void k_general_x(const uint8_t* __restrict__ pl
             const u64 later = F;
             if (later == 0ull) continue;        // the last replica: nothing left to take units from
             if (l < G && ((later >> l) & 1ull)) {
-                c.A[g * c.AS + l] -= c.x[e * G + g];
-                c.A[l * c.AS + g] -= c.x[e * G + l];
+                c.a(g, l) -= c.x[e * G + g];
+                c.a(l, g) -= c.x[e * G + l];
             }
             __syncthreads();
             while (true) {
