@@ -83,6 +83,11 @@ size_t fine_workspace_bytes(const fine_shape* shape, int which);
  * topk_w[t][:] = softmax over those K logits (fp32).
  *   x [T,d] dtype, w_router [d,E] dtype, bias [E] fp32 or NULL,
  *   topk_idx [T,K] int32 out, topk_w [T,K] fp32 out.
+ *   ws: NULL, or fine_workspace_bytes(shape, FINE_WS_TOPK) bytes of device scratch, 16-byte
+ *   aligned.  With it, bf16 layers of more than 64 experts and few tokens split the sum over i
+ *   among several thread blocks per token tile (partial logits in ws, added in ascending order of
+ *   i by a second kernel); the result is the same up to fp32 summation order.  Calls that may
+ *   overlap on the GPU need a workspace each.
  */
 int fine_topk(const fine_shape* shape, const void* x, const void* w_router, const float* bias,
               int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, void* stream);

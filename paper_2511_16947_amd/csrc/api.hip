@@ -62,7 +62,7 @@ int fine_last_hip_error(void) { return g_last_hip_error; }
 size_t fine_workspace_bytes(const fine_shape* shape, int which) {
     if (check_shape(shape) != FINE_OK) return 0;
     switch (which) {
-        case FINE_WS_TOPK: return 256;
+        case FINE_WS_TOPK: return topk_ws_bytes(*shape);
         case FINE_WS_SCHED: return sched_ws_layout(*shape).total;
         case FINE_WS_FFN: return ffn_ws_layout(*shape).total;
         case FINE_WS_BACKWARD: return bwd_ws_layout(*shape).total;
@@ -73,9 +73,9 @@ size_t fine_workspace_bytes(const fine_shape* shape, int which) {
 int fine_topk(const fine_shape* shape, const void* x, const void* w_router, const float* bias,
               int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, void* stream) {
     FINE_TRY(check_shape(shape));
-    (void)ws; (void)ws_bytes;
     if (!x || !w_router || !topk_idx || !topk_w) return FINE_INVALID_ARG;
-    return launch_topk(*shape, x, w_router, bias, topk_idx, topk_w, (hipStream_t)stream);
+    if (ws && !aligned16(ws)) return FINE_INVALID_ARG;
+    return launch_topk(*shape, x, w_router, bias, topk_idx, topk_w, ws, ws ? ws_bytes : 0, (hipStream_t)stream);
 }
 
 int fine_sched_warm(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place, const int32_t* x_prev,

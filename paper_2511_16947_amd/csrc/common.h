@@ -119,7 +119,8 @@ BwdWs bwd_ws_layout(const fine_shape& s);
 // Launchers (each enqueues on `st` and returns a FINE_* status).
 // ---------------------------------------------------------------------------
 int launch_topk(const fine_shape& s, const void* x, const void* w_router, const float* bias,
-                int32_t* topk_idx, float* topk_w, hipStream_t st);
+                int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, hipStream_t st);
+size_t topk_ws_bytes(const fine_shape& s);
 
 int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place, const int32_t* x_prev,
                  int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,

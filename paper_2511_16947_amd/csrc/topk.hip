@@ -122,13 +122,22 @@ __device__ inline void select_topk(mfma::f32x16 (&acc)[NT], const float* __restr
                                    float (*s_val)[33], int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
     const int lane = threadIdx.x & 63, r = lane & 31, h = lane >> 5;
     auto expert_of = [&](int nt, int q) { return 32 * nt + 8 * (q >> 2) + 4 * h + (q & 3); };
+    // the bias values of a tile are fetched together (an index past the end reads the last expert's
+    // again): one branch and one wait per tile, not per value
+    if (bias != nullptr) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            float b[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) b[q] = bias[min(expert_of(nt, q), E - 1)];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[nt][q] += b[q];
+        }
+    }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int e = expert_of(nt, q);
-            acc[nt][q] = (e < E) ? acc[nt][q] + (bias != nullptr ? bias[e] : 0.f) : -FLT_MAX;
-        }
+        for (int q = 0; q < 16; ++q) acc[nt][q] = (expert_of(nt, q) < E) ? acc[nt][q] : -FLT_MAX;
     for (int k = 0; k < K; ++k) {
         // position p = 16 nt + q counts the lane's values in ascending expert order
         float bv = -FLT_MAX;
@@ -143,11 +152,18 @@ __device__ inline void select_topk(mfma::f32x16 (&acc)[NT], const float* __restr
         const int oe = __shfl_xor(be, 32, 64);
         const bool partner_wins = ov > bv || (ov == bv && oe < be);
         if (partner_wins) { bv = ov; be = oe; bp = -1; }
+        // the winner leaves the race.  Its position becomes a one-hot mask and every value tests its
+        // own bit: comparing bp with each position in turn reads as a switch to the compiler, which
+        // then builds a tree of branches that the 64 lanes walk one path after another
+        constexpr int OHW = (16 * NT + 31) / 32;
+        unsigned onehot[OHW];
+#pragma unroll
+        for (int w = 0; w < OHW; ++w) onehot[w] = ((bp >> 5) == w) ? (1u << (bp & 31)) : 0u;      // bp = -1: no bit
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int q = 0; q < 16; ++q)
-                if (16 * nt + q == bp) acc[nt][q] = -FLT_MAX;
+                acc[nt][q] = ((onehot[(16 * nt + q) >> 5] >> ((16 * nt + q) & 31)) & 1u) ? -FLT_MAX : acc[nt][q];
         if (h == 0) {
             s_val[r][k] = bv;
             if (t < Tn) topk_idx[(size_t)t * K + k] = be;
@@ -265,25 +281,33 @@ __global__ __launch_bounds__(256) void k_topk_mfma(const uint16_t* __restrict__ 
 }
 
 // More than 64 experts: a block is 32 tokens and its four waves split the EXPERTS (NT / 4 tiles
-// each, every wave over the whole k range with its own slab of its experts' columns), so that
-// T / 32 blocks of four busy waves exist even when T is a few thousand.  The logits then meet in
-// LDS and wave 0 selects.
+// each, every wave with its own slab of its experts' columns), so that T / 32 blocks of four busy
+// waves exist even when T is a few thousand.  The logits then meet in LDS and wave 0 selects.
+// With a few thousand tokens even that leaves CUs idle and every block a long chain of dependent
+// steps; then gridDim.y blocks share a token tile, each over its own part of k, and write their
+// partial logits to `partial` [gridDim.y][tiles * 32][NT * 32] floats for k_topk_select.
 template <int NT>
 __global__ __launch_bounds__(256) void k_topk_mfma_esplit(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w_router,
                                                           const float* __restrict__ bias, int Tn, int d, int E, int K,
-                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                          float* __restrict__ partial) {
     using namespace mfma;
     constexpr int NTW = NT / 4;                       // expert tiles per wave
     constexpr int EPW = NTW * 32, PITCH = EPW * 2, SLAB = 64 * PITCH;
     constexpr int kLogitBytes = 32 * (NT * 32 + 1) * 4;                   // [32 tokens][experts + 1] floats
-    constexpr int kBytes = 4 * SLAB > kLogitBytes ? 4 * SLAB : kLogitBytes;
+    constexpr int kDump = 4 * SLAB;                                       // 4 x 1 KB that nobody reads
+    constexpr int XPITCH = 144, kXbuf = kDump + 4096, kXbytes = 32 * XPITCH;   // two token tiles [32][64 k], rows 16 bytes apart in banks
+    constexpr int kBytes = kXbuf + 2 * kXbytes > kLogitBytes ? kXbuf + 2 * kXbytes : kLogitBytes;
     __shared__ __attribute__((aligned(16))) char s_mem[kBytes];
     __shared__ float s_val[32][33];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 31, h = lane >> 5;
     const int t0 = blockIdx.x * 32;
-    const int tok = min(t0 + r, Tn - 1);
-    const uint16_t* xrow = x + (size_t)tok * d + 32 * h;
+    // the block's token tile of a step is fetched once, 16 bytes per thread and eight threads per token
+    // row (whole 128-byte lines), and shared through LDS; a lane's MFMA operand is token r's k-slice
+    const uint16_t* xsrc = x + (size_t)min(t0 + (int)(threadIdx.x >> 3), Tn - 1) * d + 8 * (threadIdx.x & 7);
+    const int x_st = kXbuf + (threadIdx.x >> 3) * XPITCH + 16 * (threadIdx.x & 7);
+    const int x_ld = kXbuf + r * XPITCH + 64 * h;
     const int e0 = wave * EPW;                        // this wave's first expert
 
     for (int i = threadIdx.x * 16; i < 4 * SLAB; i += 256 * 16) *reinterpret_cast<u32x4*>(s_mem + i) = u32x4{0, 0, 0, 0};
@@ -298,44 +322,74 @@ __global__ __launch_bounds__(256) void k_topk_mfma_esplit(const uint16_t* __rest
     const int tr_off = (32 * (g >> 1) + (i4 >> 2)) * PITCH + (16 * (g & 1) + 4 * (i4 & 3)) * 2;
     const int chunks = max(0, min(EPW, E - e0)) / 8;  // 16-byte pieces of this wave's part of a router-weight row
     char* slab = s_mem + wave * SLAB;
-    // as above: the next step's pieces and token values travel while this step is computed
-    constexpr int MAXP = PITCH / 16;
+    // Pieces of router-weight rows and token values are fetched DEPTH steps ahead of the step that
+    // uses them: with one block of four waves per CU nothing else hides the latency of a step's
+    // loads, and a step's MFMAs are far shorter than a trip to the L2.  No branch may sit between
+    // the loads, or every wait becomes a wait for all of them: a wave with fewer experts than
+    // pieces fetches a valid address again and drops it into a corner of LDS nobody reads, and steps
+    // past the end fetch the last step again.
+    constexpr int MAXP = PITCH / 16, DEPTH = 3;
+    const int steps_all = d / 64, steps_blk = (steps_all + (int)gridDim.y - 1) / (int)gridDim.y;
+    const int k_begin = min(steps_all, (int)blockIdx.y * steps_blk) * 64, k_end = min(steps_all, ((int)blockIdx.y + 1) * steps_blk) * 64;
     int w_off[MAXP], s_off[MAXP];
 #pragma unroll
     for (int p = 0; p < MAXP; ++p) {
         const int c = lane + 64 * p, kr = c / max(1, chunks), ce = c - kr * chunks;
-        w_off[p] = kr * E + e0 + ce * 8;
-        s_off[p] = kr * PITCH + ce * 16;
+        const bool real = p < chunks;
+        w_off[p] = real ? kr * E + e0 + ce * 8 : 0;
+        s_off[p] = real ? wave * SLAB + kr * PITCH + ce * 16 : kDump + wave * 1024 + lane * 16;
     }
-    u32x4 wreg[MAXP];
-    bf16x8 xnext[4];
-    auto fetch = [&](int k0) {
+    u32x4 wreg[DEPTH][MAXP], xreg[DEPTH];
+    // a slot's registers are re-loaded right after the LDS store that empties them: a load into other
+    // registers would have to be copied back, and the copy would wait for it
+    auto fetch = [&](auto slot, int k0) {
+        const int kc = min(k0, d - 64);                // past this block's part: some valid step again, never used
 #pragma unroll
-        for (int p = 0; p < MAXP; ++p)
-            if (p < chunks) wreg[p] = *reinterpret_cast<const u32x4*>(w_router + (size_t)k0 * E + w_off[p]);
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) xnext[kk] = *reinterpret_cast<const bf16x8*>(xrow + k0 + 8 * kk);
+        for (int p = 0; p < MAXP; ++p) wreg[slot.value][p] = *reinterpret_cast<const u32x4*>(w_router + (size_t)kc * E + w_off[p]);
+        xreg[slot.value] = *reinterpret_cast<const u32x4*>(xsrc + kc);
     };
-    fetch(0);
-    for (int k0 = 0; k0 < d; k0 += 64) {
+    static_for<DEPTH>([&](auto sl) { fetch(sl, k_begin + 64 * sl.value); });
+    auto step = [&](auto sl, int k0) {
+        const int xb = ((k0 >> 6) & 1) * kXbytes;
 #pragma unroll
-        for (int p = 0; p < MAXP; ++p)
-            if (p < chunks) *reinterpret_cast<u32x4*>(slab + s_off[p]) = wreg[p];
-        bf16x8 xf[4];
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) xf[kk] = xnext[kk];
-        if (k0 + 64 < d) fetch(k0 + 64);
+        for (int p = 0; p < MAXP; ++p) *reinterpret_cast<u32x4*>(s_mem + s_off[p]) = wreg[sl.value][p];
+        *reinterpret_cast<u32x4*>(s_mem + x_st + xb) = xreg[sl.value];
+        fetch(sl, k0 + 64 * DEPTH);
+        // everybody's piece of this step's token tile is in LDS; the other tile buffer is free again once
+        // every wave has passed this barrier (its reads belong to the step before)
+        lds_barrier();
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
+            const bf16x8 xf = *reinterpret_cast<const bf16x8*>(s_mem + x_ld + xb + 16 * kk);
 #pragma unroll
             for (int nt = 0; nt < NTW; ++nt) {
                 const char* p = slab + tr_off + (8 * kk) * PITCH + nt * 64;
                 const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)(p));
                 const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4i16_t*)(p + 4 * PITCH));
                 const bf16x8 wf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[kk], acc[nt], 0, 0, 0);
+                acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[nt], 0, 0, 0);
             }
         }
+    };
+    // whole groups of DEPTH steps run as one basic block (each slot's registers are loaded and used
+    // in place); the last one or two steps follow
+    const int steps = (k_end - k_begin) / 64, groups = steps / DEPTH;
+    for (int gi = 0; gi < groups; ++gi)
+        static_for<DEPTH>([&](auto sl) { step(sl, k_begin + (gi * DEPTH + sl.value) * 64); });
+    static_for<DEPTH - 1>([&](auto sl) {
+        if (groups * DEPTH + sl.value < steps) step(sl, k_begin + (groups * DEPTH + sl.value) * 64);
+    });
+    if (partial != nullptr) {
+        // partial logits of this block's part of k, in the accumulator's own order: four consecutive
+        // experts per store
+        float* dst = partial + ((size_t)blockIdx.y * gridDim.x * 32 + t0 + r) * (NT * 32) + e0 + 4 * h;
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4)
+                *reinterpret_cast<f32x4*>(dst + 32 * nt + 8 * q4) =
+                    f32x4{acc[nt][4 * q4], acc[nt][4 * q4 + 1], acc[nt][4 * q4 + 2], acc[nt][4 * q4 + 3]};
+        return;
     }
     // logits -> LDS [token][expert] (row length odd in floats: the 32 tokens of a wave write different banks)
     __syncthreads();
@@ -374,19 +428,104 @@ int dispatch(const fine_shape& s, const void* x, const void* w, const float* bia
 
 }  // namespace
 
+// Second pass of the gate when blocks shared token tiles.  Sixteen lanes per token, lane l holding
+// experts l, l + 16, ...: T / 4 wavefronts instead of the T / 32 that the accumulator layout gives.
+// Partial logits are added in ascending part order, then the bias; K rounds of (largest value, lowest
+// expert of equals) over the lane's values and across the sixteen lanes.
+template <int MAXJ>
+__global__ __launch_bounds__(256) void k_topk_select(const float* __restrict__ partial, int parts, int rows, int epad,
+                                                    const float* __restrict__ bias, int Tn, int E, int K,
+                                                    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    __shared__ float s_val[16][33];
+    const int grp = threadIdx.x >> 4, l = threadIdx.x & 15;
+    const int t = blockIdx.x * 16 + grp, tc = min(t, Tn - 1);
+    float v[MAXJ];
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) v[j] = 0.f;
+    for (int part = 0; part < parts; ++part) {
+        const float* src = partial + ((size_t)part * rows + tc) * epad + l;      // epad >= 16 MAXJ columns exist
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) v[j] += src[16 * j];
+    }
+    if (bias != nullptr) {
+        float b[MAXJ];
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) b[j] = bias[min(l + 16 * j, E - 1)];
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) v[j] += b[j];
+    }
+#pragma unroll
+    for (int j = 0; j < MAXJ; ++j) v[j] = (l + 16 * j < E) ? v[j] : -FLT_MAX;
+    for (int k = 0; k < K; ++k) {
+        float bv = -FLT_MAX;
+        int bj = 0;
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j)        // ">" keeps the lowest of equals
+            if (v[j] > bv) { bv = v[j]; bj = j; }
+        int be = l + 16 * bj;
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) {
+            const float ov = __shfl_xor(bv, off, 16);
+            const int oe = __shfl_xor(be, off, 16);
+            if (ov > bv || (ov == bv && oe < be)) { bv = ov; be = oe; }
+        }
+        const unsigned gone = ((be & 15) == l) ? (1u << (be >> 4)) : 0u;         // the winner leaves the race
+#pragma unroll
+        for (int j = 0; j < MAXJ; ++j) v[j] = ((gone >> j) & 1u) ? -FLT_MAX : v[j];
+        if (l == 0) {
+            s_val[grp][k] = bv;
+            if (t < Tn) topk_idx[(size_t)t * K + k] = be;
+        }
+    }
+    if (l == 0 && t < Tn) {
+        const float top = s_val[grp][0];
+        float sum = 0.f;
+        for (int k = 0; k < K; ++k) sum += __expf(s_val[grp][k] - top);
+        for (int k = 0; k < K; ++k) topk_w[(size_t)t * K + k] = __expf(s_val[grp][k] - top) / sum;
+    }
+}
+
+// Parts of k that blocks of one token tile split among themselves: enough blocks for two per CU,
+// at least eight steps of 64 k each, at most eight parts.
+int topk_parts(const fine_shape& s) {
+    if (s.dtype != FINE_BF16 || s.E <= 64 || s.E > 256 || s.E % 8 != 0 || s.d % 64 != 0 || s.T == 0) return 1;
+    const int tiles = cdiv(s.T, 32);
+    return max(1, min(min(8, cdiv(512, tiles)), s.d / 64 / 8));
+}
+
+size_t topk_ws_bytes(const fine_shape& s) {
+    const int parts = topk_parts(s);
+    if (parts == 1) return 256;
+    return align_up((size_t)parts * cdiv(s.T, 32) * 32 * (s.E <= 128 ? 128 : 256) * sizeof(float), 256);
+}
+
 int launch_topk(const fine_shape& s, const void* x, const void* w_router, const float* bias,
-                int32_t* topk_idx, float* topk_w, hipStream_t st) {
+                int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, hipStream_t st) {
     if (s.T == 0) return FINE_OK;
     if (s.dtype == FINE_F32) return dispatch<float>(s, x, w_router, bias, topk_idx, topk_w, st);
     if (s.E % 8 == 0 && s.E <= 256 && s.d % 64 == 0) {
 #define FINE_TOPK_MFMA(KERNEL)                                                                                  \
     hipLaunchKernelGGL((KERNEL), dim3(cdiv(s.T, 32)), dim3(256), 0, st, (const uint16_t*)x,                     \
                        (const uint16_t*)w_router, bias, s.T, s.d, s.E, s.K, topk_idx, topk_w)
+#define FINE_TOPK_ESPLIT(NT)                                                                                    \
+    do {                                                                                                        \
+        hipLaunchKernelGGL((k_topk_mfma_esplit<NT>), dim3(cdiv(s.T, 32), parts), dim3(256), 0, st,              \
+                           (const uint16_t*)x, (const uint16_t*)w_router, bias, s.T, s.d, s.E, s.K, topk_idx,  \
+                           topk_w, parts > 1 ? (float*)ws : nullptr);                                           \
+        if (parts > 1) {                                                                                        \
+            FINE_LAUNCH_CHECK();                                                                                \
+            hipLaunchKernelGGL((k_topk_select<2 * NT>), dim3(cdiv(s.T, 16)), dim3(256), 0, st, (const float*)ws, \
+                               parts, cdiv(s.T, 32) * 32, NT * 32, bias, s.T, s.E, s.K, topk_idx, topk_w);      \
+        }                                                                                                       \
+    } while (0)
+        // without the workspace for the partial logits every token tile is one block's
+        const int parts = (ws != nullptr && ws_bytes >= topk_ws_bytes(s)) ? topk_parts(s) : 1;
         if (s.E <= 32) FINE_TOPK_MFMA(k_topk_mfma<1>);
         else if (s.E <= 64) FINE_TOPK_MFMA(k_topk_mfma<2>);
-        else if (s.E <= 128) FINE_TOPK_MFMA(k_topk_mfma_esplit<4>);
-        else FINE_TOPK_MFMA(k_topk_mfma_esplit<8>);
+        else if (s.E <= 128) FINE_TOPK_ESPLIT(4);
+        else FINE_TOPK_ESPLIT(8);
 #undef FINE_TOPK_MFMA
+#undef FINE_TOPK_ESPLIT
         FINE_LAUNCH_CHECK();
         return FINE_OK;
     }

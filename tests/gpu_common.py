@@ -47,11 +47,12 @@ class GpuLayer:
         self.y_perm = torch.empty(s.P, s.d, dtype=s.torch_dtype, device=dev)
         self.out = torch.empty(s.T, s.d, dtype=s.torch_dtype, device=dev)
         self.ws_ffn = fm.alloc_workspace(s, fm.WS_FFN, dev)
+        self.ws_topk = fm.alloc_workspace(s, fm.WS_TOPK, dev)
         self.act_save = None
 
     def topk(self):
         i = self.inp
-        fm.fine_topk(self.shape, i.x, i.w_router, i.bias, self.topk_idx, self.topk_w)
+        fm.fine_topk(self.shape, i.x, i.w_router, i.bias, self.topk_idx, self.topk_w, self.ws_topk)
 
     def sched(self, place=None):
         self.sb.run(self.shape, self.topk_idx, place)

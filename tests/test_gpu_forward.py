@@ -64,6 +64,9 @@ ROUTER_CASES = [
     (257, 448, 64, 6, "bf16"),     # two expert tiles, k-steps not a multiple of 4
     (300, 192, 128, 8, "bf16"),    # MFMA, block shares the slab; T not a multiple of 128
     (129, 128, 256, 8, "bf16"),    # eight expert tiles
+    (700, 1024, 256, 8, "bf16"),   # few token tiles, long k: blocks share a tile, 2 parts of k (with the workspace)
+    (130, 1600, 96, 4, "bf16"),    # 3 parts of 9, 9, 7 steps; E = 96: the fourth wave of a block has no experts
+    (40, 4608, 160, 5, "bf16"),    # 8 parts of 9 steps; E = 160 on the 256-expert kernel: waves 2 and 3 partly or wholly idle
     (64, 128, 24, 1, "bf16"),      # E a multiple of 8 but not of 32, K = 1
     (200, 128, 12, 3, "bf16"),     # E not a multiple of 8: lane-per-expert kernel
     (77, 50, 5, 2, "f32"),         # fp32
@@ -78,13 +81,17 @@ def test_router_topk(case):
     shape = fm.shape_of(cfg)
     idx = torch.full((T, K), -1, dtype=torch.int32, device=DEV)
     w = torch.full((T, K), -1.0, dtype=torch.float32, device=DEV)
-    print("router case", case, flush=True)
-    fm.fine_topk(shape, inp.x, inp.w_router, inp.bias, idx, w)
-    torch.cuda.synchronize()
-    check_router(cfg, inp, idx, w)
-    got = idx.cpu().numpy()
-    assert got.min() >= 0 and got.max() < E
-    assert np.allclose(to64(w).sum(axis=1), 1.0, atol=1e-5)
+    # without and with the workspace (which lets blocks share a token tile when tokens are few)
+    for ws in (None, fm.alloc_workspace(shape, fm.WS_TOPK, DEV)):
+        print("router case", case, "workspace", None if ws is None else ws.numel(), flush=True)
+        idx.fill_(-1)
+        w.fill_(-1.0)
+        fm.fine_topk(shape, inp.x, inp.w_router, inp.bias, idx, w, ws)
+        torch.cuda.synchronize()
+        check_router(cfg, inp, idx, w)
+        got = idx.cpu().numpy()
+        assert got.min() >= 0 and got.max() < E
+        assert np.allclose(to64(w).sum(axis=1), 1.0, atol=1e-5)
 
 
 # ------------------------------------------------------------------ whole layer, small

@@ -130,10 +130,11 @@ def test_scheduling_on_a_second_stream_gives_the_in_line_results():
     y_perm = torch.empty(s.P, s.d, dtype=s.torch_dtype, device=DEV)
     outs = [torch.empty(s.T, s.d, dtype=s.torch_dtype, device=DEV) for _ in range(n)]
     ws_ffn = fm.alloc_workspace(s, fm.WS_FFN, DEV)
+    ws_topk = fm.alloc_workspace(s, fm.WS_TOPK, DEV)       # one: the gate calls follow each other on the side stream
 
     def gate_and_schedule(i):
         b, sb = i & 1, sbs[i & 1]
-        fm.fine_topk(s, inp.x, inp.w_router, biases[i], topk_idx[b], topk_w[b])
+        fm.fine_topk(s, inp.x, inp.w_router, biases[i], topk_idx[b], topk_w[b], ws_topk)
         fm.fine_sched_warm(s, topk_idx[b], place, sbs[b ^ 1].x_eg if i > 0 else None, sb.load, sb.input_eg, sb.x_eg,
                            sb.max_load, sb.pair_dst, sb.row_of_pair, sb.pair_of_row, sb.seg_off, sb.rank_off, sb.ws)
 
