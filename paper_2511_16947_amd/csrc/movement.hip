@@ -22,7 +22,17 @@ __global__ __launch_bounds__(256) void k_permute_vec(const char* __restrict__ x,
     const u32x4* src = reinterpret_cast<const u32x4*>(x + (size_t)t * row_bytes);
     u32x4* dst = reinterpret_cast<u32x4*>(x_perm + (size_t)row * row_bytes);
     const int n = row_bytes >> 4;
-    for (int i = lane; i < n; i += 64) dst[i] = src[i];
+    // eight loads in flight per lane (8 KB of a row per pass), no branch between them: a piece index
+    // past the end reads the last piece again and is not stored
+    constexpr int U = 8;
+    for (int i0 = lane; i0 < n; i0 += 64 * U) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = src[min(i0 + 64 * u, n - 1)];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (i0 + 64 * u < n) dst[i0 + 64 * u] = v[u];
+    }
 }
 
 template <typename T>
@@ -36,7 +46,57 @@ __global__ __launch_bounds__(256) void k_permute_scalar(const T* __restrict__ x,
 }
 
 // ---- combine: out[t] = sum_k w[t][k] * y_perm[row_of_pair[t*K+k]] -----------------
-// One wave per token, each lane owns groups of VEC consecutive columns.
+// One wave per token, each lane owns groups of VEC consecutive columns.  KMAX > 0: K <= KMAX and
+// 16-byte groups; the token's rows and weights are read once, the KMAX loads of U groups are all in
+// flight before the first is used (k past K reads the last row again and is not added), and the sum
+// runs in ascending k as in the plain loop below, so both give the same bits.
+template <typename T, int KMAX, int U, bool UNIT = false>      // UNIT: all weights 1 (topk_w is not read)
+__global__ __launch_bounds__(256) void k_combine_rows(const T* __restrict__ y_perm, const int32_t* __restrict__ row_of_pair,
+                                                      const float* __restrict__ topk_w, T* __restrict__ out,
+                                                      int Tn, int K, int d) {
+    constexpr int VEC = 16 / sizeof(T);
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= Tn) return;
+    const int lane = threadIdx.x & 63;
+    const u32x4* src[KMAX];
+    float w[KMAX];
+#pragma unroll
+    for (int k = 0; k < KMAX; ++k) {
+        const int kc = min(k, K - 1);
+        src[k] = reinterpret_cast<const u32x4*>(y_perm + (size_t)row_of_pair[(size_t)t * K + kc] * d);
+        w[k] = UNIT ? 1.f : topk_w[(size_t)t * K + kc];
+    }
+    u32x4* dst = reinterpret_cast<u32x4*>(out + (size_t)t * d);
+    const int n = d / VEC;
+    for (int i0 = lane; i0 < n; i0 += 64 * U) {
+        u32x4 v[U][KMAX];
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) v[u][k] = src[k][min(i0 + 64 * u, n - 1)];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            float acc[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+#pragma unroll
+            for (int k = 0; k < KMAX; ++k) {
+                alignas(16) T tmp[VEC];
+                *reinterpret_cast<u32x4*>(tmp) = v[u][k];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const float a = fmaf(w[k], Elem<T>::load(&tmp[e]), acc[e]);
+                    acc[e] = (k < K) ? a : acc[e];
+                }
+            }
+            alignas(16) T res[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) Elem<T>::store(&res[e], acc[e]);
+            if (i0 + 64 * u < n) dst[i0 + 64 * u] = *reinterpret_cast<u32x4*>(res);
+        }
+    }
+}
+
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void k_combine(const T* __restrict__ y_perm, const int32_t* __restrict__ row_of_pair,
                                                  const float* __restrict__ topk_w, T* __restrict__ out,
@@ -89,27 +149,51 @@ __global__ __launch_bounds__(256) void k_combine_bwd(const T* __restrict__ d_out
     const int t = p / K;
     const float w = topk_w[p];
     float dot = 0.f;
-    for (int c = lane * VEC; c < d; c += 64 * VEC) {
-        alignas(16) T g[VEC]; alignas(16) T y[VEC]; alignas(16) T o[VEC];
-        const T* gs = d_out + (size_t)t * d + c;
-        const T* ys = y_perm + (size_t)row * d + c;
-        if (VEC * sizeof(T) == 16) {
-            *reinterpret_cast<u32x4*>(g) = *reinterpret_cast<const u32x4*>(gs);
-            *reinterpret_cast<u32x4*>(y) = *reinterpret_cast<const u32x4*>(ys);
-        } else {
+    if (VEC * sizeof(T) == 16) {
+        // four groups of both rows in flight per lane; groups are taken in the order of the plain
+        // loop, so the dot product keeps its bits
+        constexpr int U = 4;
+        const u32x4* gs = reinterpret_cast<const u32x4*>(d_out + (size_t)t * d);
+        const u32x4* ys = reinterpret_cast<const u32x4*>(y_perm + (size_t)row * d);
+        u32x4* dst = reinterpret_cast<u32x4*>(dy_perm + (size_t)row * d);
+        const int n = d / VEC;
+        for (int i0 = lane; i0 < n; i0 += 64 * U) {
+            u32x4 gv4[U], yv4[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                gv4[u] = gs[min(i0 + 64 * u, n - 1)];
+                yv4[u] = ys[min(i0 + 64 * u, n - 1)];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                alignas(16) T g[VEC]; alignas(16) T y[VEC]; alignas(16) T o[VEC];
+                *reinterpret_cast<u32x4*>(g) = gv4[u];
+                *reinterpret_cast<u32x4*>(y) = yv4[u];
+                const bool in = i0 + 64 * u < n;
+#pragma unroll
+                for (int v = 0; v < VEC; ++v) {
+                    const float gv = Elem<T>::load(&g[v]);
+                    const float nd = fmaf(gv, Elem<T>::load(&y[v]), dot);
+                    dot = in ? nd : dot;
+                    Elem<T>::store(&o[v], w * gv);
+                }
+                if (in) dst[i0 + 64 * u] = *reinterpret_cast<u32x4*>(o);
+            }
+        }
+    } else {
+        for (int c = lane * VEC; c < d; c += 64 * VEC) {
+            alignas(16) T g[VEC]; alignas(16) T y[VEC]; alignas(16) T o[VEC];
+            const T* gs = d_out + (size_t)t * d + c;
+            const T* ys = y_perm + (size_t)row * d + c;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) { g[v] = gs[v]; y[v] = ys[v]; }
-        }
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) {
-            const float gv = Elem<T>::load(&g[v]);
-            dot = fmaf(gv, Elem<T>::load(&y[v]), dot);
-            Elem<T>::store(&o[v], w * gv);
-        }
-        T* dst = dy_perm + (size_t)row * d + c;
-        if (VEC * sizeof(T) == 16) {
-            *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<u32x4*>(o);
-        } else {
+            for (int v = 0; v < VEC; ++v) {
+                const float gv = Elem<T>::load(&g[v]);
+                dot = fmaf(gv, Elem<T>::load(&y[v]), dot);
+                Elem<T>::store(&o[v], w * gv);
+            }
+            T* dst = dy_perm + (size_t)row * d + c;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) dst[v] = o[v];
         }
@@ -190,13 +274,24 @@ int launch_permute(const fine_shape& s, const void* x, const int32_t* pair_of_ro
 int launch_combine(const fine_shape& s, const void* y_perm, const int32_t* row_of_pair,
                    const float* topk_w, void* out, hipStream_t st) {
     if (s.T == 0) return FINE_OK;
-    if (s.dtype == FINE_F32) {
-        auto* y = (const float*)y_perm; auto* o = (float*)out;
-        FINE_DISPATCH_ROWS(k_combine, float, s.T, y, row_of_pair, topk_w, o, s.T, s.K, s.d);
-    } else {
-        auto* y = (const uint16_t*)y_perm; auto* o = (uint16_t*)out;
-        FINE_DISPATCH_ROWS(k_combine, uint16_t, s.T, y, row_of_pair, topk_w, o, s.T, s.K, s.d);
-    }
+    // rows of whole 16-byte groups and at most 8 experts per token: the kernel that keeps all of a
+    // group's loads in flight (8 per lane: 4 groups x 2 rows, 2 x 4 or 1 x 8)
+#define FINE_COMBINE_ROWS(TYPE)                                                                                 \
+    do {                                                                                                        \
+        auto* y = (const TYPE*)y_perm; auto* o = (TYPE*)out;                                                    \
+        const dim3 grid(cdiv(s.T, 4)), block(256);                                                              \
+        if (s.d % (16 / sizeof(TYPE)) != 0 || s.K > 8)                                                          \
+            FINE_DISPATCH_ROWS(k_combine, TYPE, s.T, y, row_of_pair, topk_w, o, s.T, s.K, s.d);                 \
+        else if (s.K <= 2)                                                                                      \
+            hipLaunchKernelGGL((k_combine_rows<TYPE, 2, 4>), grid, block, 0, st, y, row_of_pair, topk_w, o, s.T, s.K, s.d); \
+        else if (s.K <= 4)                                                                                      \
+            hipLaunchKernelGGL((k_combine_rows<TYPE, 4, 2>), grid, block, 0, st, y, row_of_pair, topk_w, o, s.T, s.K, s.d); \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_combine_rows<TYPE, 8, 1>), grid, block, 0, st, y, row_of_pair, topk_w, o, s.T, s.K, s.d); \
+    } while (0)
+    if (s.dtype == FINE_F32) FINE_COMBINE_ROWS(float);
+    else FINE_COMBINE_ROWS(uint16_t);
+#undef FINE_COMBINE_ROWS
     FINE_LAUNCH_CHECK();
     return FINE_OK;
 }
@@ -220,13 +315,24 @@ int launch_combine_bwd(const fine_shape& s, const void* d_out, const void* y_per
 int launch_permute_bwd(const fine_shape& s, const void* dx_perm, const int32_t* row_of_pair,
                        void* d_x, hipStream_t st) {
     if (s.T == 0) return FINE_OK;
-    if (s.dtype == FINE_F32) {
-        auto* g = (const float*)dx_perm; auto* o = (float*)d_x;
-        FINE_DISPATCH_ROWS(k_permute_bwd, float, s.T, g, row_of_pair, o, s.T, s.K, s.d);
-    } else {
-        auto* g = (const uint16_t*)dx_perm; auto* o = (uint16_t*)d_x;
-        FINE_DISPATCH_ROWS(k_permute_bwd, uint16_t, s.T, g, row_of_pair, o, s.T, s.K, s.d);
-    }
+    // as in launch_combine, with unit weights (a product by 1 is exact, so the sums keep their bits)
+#define FINE_PERMUTE_BWD_ROWS(TYPE)                                                                             \
+    do {                                                                                                        \
+        auto* g = (const TYPE*)dx_perm; auto* o = (TYPE*)d_x;                                                   \
+        const dim3 grid(cdiv(s.T, 4)), block(256);                                                              \
+        const float* none = nullptr;                                                                            \
+        if (s.d % (16 / sizeof(TYPE)) != 0 || s.K > 8)                                                          \
+            FINE_DISPATCH_ROWS(k_permute_bwd, TYPE, s.T, g, row_of_pair, o, s.T, s.K, s.d);                     \
+        else if (s.K <= 2)                                                                                      \
+            hipLaunchKernelGGL((k_combine_rows<TYPE, 2, 4, true>), grid, block, 0, st, g, row_of_pair, none, o, s.T, s.K, s.d); \
+        else if (s.K <= 4)                                                                                      \
+            hipLaunchKernelGGL((k_combine_rows<TYPE, 4, 2, true>), grid, block, 0, st, g, row_of_pair, none, o, s.T, s.K, s.d); \
+        else                                                                                                    \
+            hipLaunchKernelGGL((k_combine_rows<TYPE, 8, 1, true>), grid, block, 0, st, g, row_of_pair, none, o, s.T, s.K, s.d); \
+    } while (0)
+    if (s.dtype == FINE_F32) FINE_PERMUTE_BWD_ROWS(float);
+    else FINE_PERMUTE_BWD_ROWS(uint16_t);
+#undef FINE_PERMUTE_BWD_ROWS
     FINE_LAUNCH_CHECK();
     return FINE_OK;
 }
