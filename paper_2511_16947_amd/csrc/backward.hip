@@ -55,21 +55,21 @@ __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, con
         struct PreAct {
             uint2 a4, b4;
         };
+        // a group outside the tile reads the last valid group again (no branch around the loads) and is
+        // not stored
         auto fetch_act = [&](int m, int c) {
-            PreAct p{make_uint2(0u, 0u), make_uint2(0u, 0u)};
-            const int col = n0 + c;
-            if (m < te.rows && col < f) {
-                const size_t row = (size_t)te.row0 + m;
-                p.a4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + col);
-                p.b4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + f + col);
-            }
+            const size_t row = (size_t)te.row0 + min(m, te.rows - 1);
+            const int col = min(n0 + c, f - 4);
+            PreAct p;
+            p.a4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + col);
+            p.b4 = *reinterpret_cast<const uint2*>(act + row * (size_t)(2 * f) + f + col);
             return p;
         };
-        auto swiglu_bwd = [&](int m, int c, uint2 dh4, uint2 a4, uint2 b4) {
-            const int col = n0 + c;
-            if (m >= te.rows || col >= f) return;
-            const size_t row = (size_t)te.row0 + m;
-            const uint32_t dhw[2] = {dh4.x, dh4.y}, aw[2] = {a4.x, a4.y}, bw[2] = {b4.x, b4.y};
+        struct Grads {
+            uint2 da, db, hh;
+        };
+        auto swiglu_bwd = [&](int, int, uint2 dh4, const PreAct& p) {
+            const uint32_t dhw[2] = {dh4.x, dh4.y}, aw[2] = {p.a4.x, p.a4.y}, bw[2] = {p.b4.x, p.b4.y};
             uint32_t da[2], db[2], hh[2];
 #pragma unroll
             for (int w = 0; w < 2; ++w) {
@@ -88,18 +88,22 @@ __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, con
                 db[w] = pack_bf16x2(o_db[0], o_db[1]);
                 hh[w] = pack_bf16x2(o_h[0], o_h[1]);
             }
-            *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + col) = make_uint2(da[0], da[1]);
-            *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + f + col) = make_uint2(db[0], db[1]);
-            *reinterpret_cast<uint2*>(h + row * (size_t)f + col) = make_uint2(hh[0], hh[1]);
+            return Grads{make_uint2(da[0], da[1]), make_uint2(db[0], db[1]), make_uint2(hh[0], hh[1])};
+        };
+        auto store_grads = [&](int m, int c, const Grads& g) {
+            const int col = n0 + c;
+            if (m >= te.rows || col >= f) return;
+            const size_t row = (size_t)te.row0 + m;
+            *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + col) = g.da;
+            *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + f + col) = g.db;
+            *reinterpret_cast<uint2*>(h + row * (size_t)f + col) = g.hh;
         };
         auto acc_val = [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; };
         if constexpr (W8)
-            stage_tile_bf16_fetch<WAVES_M, WAVES_N, WM, WN, WMC>(
-                smem, acc_val, fetch_act, [&](int m, int c, uint2 dh4, const PreAct& p) { swiglu_bwd(m, c, dh4, p.a4, p.b4); });
+            stage_tile_bf16_fetch<WAVES_M, WAVES_N, WM, WN, WMC>(smem, acc_val, fetch_act, swiglu_bwd, store_grads);
         else
             stage_tile_bf16<WAVES_M, WAVES_N, WM, WN, WMC>(smem, acc_val, [&](int m, int c, uint2 dh4) {
-                const PreAct p = fetch_act(m, c);
-                swiglu_bwd(m, c, dh4, p.a4, p.b4);
+                store_grads(m, c, swiglu_bwd(m, c, dh4, fetch_act(m, c)));
             });
     }
 }
@@ -250,14 +254,13 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
         stage_tile_f32<WAVES_M, WAVES_N, WM, WN>(
             smem, acc,
             [&](int r, int c) {
-                const int m = m0 + r, col = n0 + c;
-                if (accumulate && m < p.M && col < p.N) return *reinterpret_cast<const float4*>(out + (size_t)m * p.N + col);
-                return make_float4(0.f, 0.f, 0.f, 0.f);
+                // outside the tile the last valid group is read again (no branch around the load) and not stored
+                if (!accumulate) return make_float4(0.f, 0.f, 0.f, 0.f);      // the same for every thread
+                return *reinterpret_cast<const float4*>(out + (size_t)min(m0 + r, p.M - 1) * p.N + min(n0 + c, p.N - 4));
             },
-            [&](int r, int c, float4 v, float4 o) {
+            [&](int r, int c, float4 v) {
                 const int m = m0 + r, col = n0 + c;
                 if (m >= p.M || col >= p.N) return;
-                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
                 *reinterpret_cast<float4*>(out + (size_t)m * p.N + col) = v;
             });
     }

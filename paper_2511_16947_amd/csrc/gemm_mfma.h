@@ -207,11 +207,13 @@ __device__ inline void stage_tile_bf16(char* smem, Val val, Emit emit) {
 }
 
 // The same for an epilogue that also reads global memory: fetch(row, col) starts the reads of a
-// group of four columns and returns what they deliver, emit(row, col, values, fetched) uses them.
-// The reads of eight groups are started before the first is used, so a thread waits for memory
-// twice per pass instead of once per group.
-template <int WAVES_M, int WAVES_N, int WM, int NT, int WMC, typename Val, typename Fetch, typename Emit>
-__device__ inline void stage_tile_bf16_fetch(char* smem, Val val, Fetch fetch, Emit emit) {
+// group of four columns and returns what they deliver, compute(row, col, values, fetched) turns them
+// into what store(row, col, result) writes.  Eight groups at a time: all reads are started before the
+// first is used, so a thread waits for memory once per eight groups instead of once per group.  fetch
+// must not branch around its loads (clamp the address instead): a load inside a branch is followed by
+// a wait for everything outstanding, which turns the eight reads back into eight round trips.
+template <int WAVES_M, int WAVES_N, int WM, int NT, int WMC, typename Val, typename Fetch, typename Compute, typename Store>
+__device__ inline void stage_tile_bf16_fetch(char* smem, Val val, Fetch fetch, Compute compute, Store store) {
     constexpr int BNC = WAVES_N * NT * 32;
     constexpr int PITCH = BNC * 2 + 8;
     constexpr int ROWS_PASS = WAVES_M * WMC * 32;
@@ -245,10 +247,15 @@ __device__ inline void stage_tile_bf16_fetch(char* smem, Val val, Fetch fetch, E
                 const int u = u0 + j.value * THREADS;
                 got[j.value] = fetch(row_of(u), (u % (BNC / 4)) * 4);
             });
+            decltype(compute(0, 0, uint2{}, got[0])) res[AHEAD];
             static_for<AHEAD>([&](auto j) {
                 const int u = u0 + j.value * THREADS;
                 const int crow = u / (BNC / 4), cu = u % (BNC / 4);
-                emit(row_of(u), cu * 4, *reinterpret_cast<const uint2*>(smem + crow * PITCH + cu * 8), got[j.value]);
+                res[j.value] = compute(row_of(u), cu * 4, *reinterpret_cast<const uint2*>(smem + crow * PITCH + cu * 8), got[j.value]);
+            });
+            static_for<AHEAD>([&](auto j) {
+                const int u = u0 + j.value * THREADS;
+                store(row_of(u), (u % (BNC / 4)) * 4, res[j.value]);
             });
         }
         lds_barrier();
@@ -259,8 +266,9 @@ __device__ inline void stage_tile_bf16_fetch(char* smem, Val val, Fetch fetch, E
 // (rows of BN floats + 16 bytes, so that the 16-byte writes of 16 lanes cover all banks), then
 // emit(row, col, four values) is called with a wave covering 256 consecutive floats of one row:
 // 16-byte stores that fill whole cache lines instead of 32-byte pieces of 32 different rows.
-// fetch(row, col) may start a read of the four old values (accumulation); all of a pass's reads
-// are started before the first is used.
+// fetch(row, col) returns the four old values to add (zeros when nothing is accumulated; it must not
+// branch around its load); all of a pass's reads are started, then all sums are formed, then
+// emit(row, col, four sums) stores them.
 template <int WAVES_M, int WAVES_N, int WM, int WN, typename Fetch, typename Emit>
 __device__ inline void stage_tile_f32(char* smem, const f32x16 (&acc)[WM][WN], Fetch fetch, Emit emit) {
     constexpr int BN = WAVES_N * WN * 32;
@@ -287,11 +295,17 @@ __device__ inline void stage_tile_f32(char* smem, const f32x16 (&acc)[WM][WN], F
             const int cr = u / (BN / 4);
             old[j.value] = fetch(((cr / 32) * WM + mi.value) * 32 + cr % 32, (u % (BN / 4)) * 4);
         });
-        static_for<PER>([&](auto j) {
+        float4 sum[PER];
+        static_for<PER>([&](auto j) {                     // every fetched value is used before the first store
             const int u = threadIdx.x + j.value * THREADS;
             const int cr = u / (BN / 4), cu = u % (BN / 4);
-            emit(((cr / 32) * WM + mi.value) * 32 + cr % 32, cu * 4,
-                 *reinterpret_cast<const float4*>(smem + cr * PITCH + cu * 16), old[j.value]);
+            const float4 v = *reinterpret_cast<const float4*>(smem + cr * PITCH + cu * 16), o = old[j.value];
+            sum[j.value] = make_float4(v.x + o.x, v.y + o.y, v.z + o.z, v.w + o.w);
+        });
+        static_for<PER>([&](auto j) {
+            const int u = threadIdx.x + j.value * THREADS;
+            const int cr = u / (BN / 4);
+            emit(((cr / 32) * WM + mi.value) * 32 + cr % 32, (u % (BN / 4)) * 4, sum[j.value]);
         });
         lds_barrier();
     });
