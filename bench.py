@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # Counter readings of the GEMM 1 kernel (mean KiB per launch over a default run of this file under
 # rocprofv3 --pmc; profiles/ffn_gemm1_w8_cfg2_mixtral_hbm_counters.md), scaled by what the same
 # counters read for --copy-calibration: FETCH_SIZE 0.5 per byte read, WRITE_SIZE 1.0 per byte written.
-GEMM1_TRAFFIC_BYTES = {"cfg2_mixtral": int(688368.0 * 1024 * 2.0 + 96261.2 * 1024 * 1.0)}
+GEMM1_TRAFFIC_BYTES = {"cfg2_mixtral": int(687043.3 * 1024 * 2.0 + 96261.2 * 1024 * 1.0)}
 
 
 def parse():
