@@ -42,6 +42,16 @@ def test_version_and_workspace_queries(lib):
     assert fm.fine_workspace_bytes(fm.Shape(250, 128, 256, 8, 2, 4, fm.FINE_F32), fm.WS_SCHED) == 0
     assert fm.fine_workspace_bytes(fm.Shape(256, 128, 256, 2, 3, 4, fm.FINE_F32), fm.WS_SCHED) == 0
     assert fm.fine_workspace_bytes(fm.Shape(256, 100, 256, 8, 2, 4, fm.FINE_BF16), fm.WS_FFN) == 0
+    # the gate's workspace: room for the partial logits when blocks share a token tile (bf16, more than
+    # 64 experts, few tokens, a long enough k range), a token amount otherwise
+    gate = lambda T, d, E, dt=fm.FINE_BF16: fm.fine_workspace_bytes(fm.Shape(T, d, 64, E, 2, 1, dt), fm.WS_TOPK)
+    assert gate(4096, 7168, 256) == 4 * 4096 * 256 * 4          # 128 tiles: 4 parts of the 112 steps
+    assert gate(4096, 2048, 128) == 4 * 4096 * 128 * 4          # 32 steps: 4 parts of 8
+    assert gate(40, 4608, 160) == 8 * 64 * 256 * 4              # 2 tiles of 32 tokens, 8 parts; 160 experts padded to 256
+    assert gate(4096, 512, 256) == 256                          # 8 steps: not worth splitting
+    assert gate(32768, 7168, 256) == 256                        # 1024 tiles fill the chip
+    assert gate(4096, 7168, 64) == 256                          # 64 experts: the waves of a block split k already
+    assert gate(4096, 7168, 256, fm.FINE_F32) == 256
 
 
 def test_null_pointers_are_rejected_without_touching_the_gpu(lib):
