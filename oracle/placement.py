@@ -24,9 +24,8 @@ Readings where the paper is silent:
   * the keys come from a counter-based generator (below) so that any
     implementation draws the same candidates from (seed, candidate index);
   * among candidates of equal m the lowest index wins;
-  * Eq. 3 enumerates 2^G - 1 subsets; for more than 16 ranks the score is the
-    integer optimum M* = ceil(m) of Eq. 1 instead (exact max-flow bisection), so
-    candidates whose m differ by less than one token tie.
+  * Eq. 3 enumerates 2^G - 1 subsets; for more than 16 ranks the same m comes
+    from exact max-flow tests instead (sched.lp_optimum_by_flows).
 """
 from fractions import Fraction
 
@@ -93,15 +92,12 @@ def draw_placement(counts, G: int, slots: int, seed: int, cand: int) -> np.ndarr
 
 
 def max_density(load, place) -> Fraction:
-    """m of Eq. 3 for one placement (G <= 16); M* = ceil(m) for wider ones."""
+    """m of Eq. 3 for one placement: by enumeration up to 16 ranks, by flows beyond."""
     load = np.asarray(load, dtype=np.int64)
     place = np.asarray(place)
     if place.shape[1] <= 16:
         return sched.lp_optimum_eq3(load, place)
-    for e in range(len(load)):
-        if load[e] > 0 and not place[e].any():
-            raise ValueError("expert %d has load but no replica" % e)
-    return Fraction(sched.min_max_load(load, place))
+    return sched.lp_optimum_by_flows(load, place)
 
 
 def search(load, G: int, slots: int, n: int, seed: int):

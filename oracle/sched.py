@@ -145,6 +145,36 @@ def min_max_load(load: np.ndarray, place: np.ndarray) -> int:
     return lo
 
 
+def lp_optimum_by_flows(load: np.ndarray, place: np.ndarray) -> Fraction:
+    """m of Eq. 1 / Eq. 3 as an exact fraction without enumerating the 2^G - 1
+    subsets of Eq. 3 (for placements on more than 16 ranks).
+
+    m = load(S*) / |S*| for some set S* of ranks, so its denominator b is at most
+    G.  For a fixed b, Eq. 1 with every load multiplied by b and rank loads
+    bounded by an integer a is an integer transportation problem, feasible
+    exactly when a / b >= m; its least feasible a is ceil(m b), found by
+    bisection with the max-flow test between (M* - 1) b (too small: m > M* - 1)
+    and M* b (enough).  Hence m = min over b of ceil(m b) / b, the minimum being
+    attained at b = |S*|."""
+    E, G = place.shape
+    load = np.asarray(load, dtype=np.int64)
+    if int(load.sum()) == 0:
+        return Fraction(0)
+    M = min_max_load(load, place)
+    allowed = place.astype(bool)
+    best = Fraction(M)
+    for b in range(2, G + 1):
+        lo, hi = (M - 1) * b + 1, M * b
+        while lo < hi:
+            mid = (lo + hi) // 2
+            if _flow_saturates(load * b, allowed, np.full(G, mid, dtype=np.int64)):
+                hi = mid
+            else:
+                lo = mid + 1
+        best = min(best, Fraction(lo, b))
+    return best
+
+
 # --------------------------------------------------------------------------
 # replica loads
 # --------------------------------------------------------------------------

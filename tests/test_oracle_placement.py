@@ -156,3 +156,57 @@ def test_zipf_experiment_asymmetric_placement_balances_completely():
         counts, scores, best, place = placement.search(load, G, slots, 32, 0)
         assert scores[best] == Fraction(P, G), (s, scores[best])
         assert sched.min_max_load(load, place) == P // G
+
+
+def test_density_by_flows_equals_the_enumeration_of_eq3():
+    """The flow-based m (used beyond 16 ranks, where Eq. 3's subsets cannot be listed) against Eq. 3
+    written out, on placements small enough for both: random masks with 1-4 replicas per expert,
+    skewed loads, loads of zero, and one closed group of ranks that carries most of the load (so
+    that m is a fraction with a denominator well below G)."""
+    rng = np.random.default_rng(123)
+    seen_fraction = False
+    for trial in range(40):
+        G = int(rng.integers(2, 10)); E = int(rng.integers(1, 14))
+        place = np.zeros((E, G), dtype=np.uint8)
+        for e in range(E):
+            place[e, rng.choice(G, size=int(rng.integers(1, min(G, 4) + 1)), replace=False)] = 1
+        load = (rng.pareto(1.2, size=E) * 20).astype(np.int64)
+        load[rng.random(E) < 0.2] = 0
+        if trial % 4 == 0 and G >= 4:                 # experts 0..1 live on ranks 0..2 only and are hot
+            place[:2] = 0
+            place[:2, :3] = 1
+            load[:2] += 500 + trial
+        want = sched.lp_optimum_eq3(load, place)
+        got = sched.lp_optimum_by_flows(load, place)
+        assert got == want, (trial, load.tolist(), place.tolist(), got, want)
+        seen_fraction = seen_fraction or want.denominator > 1
+    assert seen_fraction
+
+
+def test_density_by_flows_on_a_wide_placement_against_highs():
+    """24 ranks: Eq. 3 cannot be listed; HiGHS on Eq. 1 gives m to solver precision, and the exact
+    fraction must be the one with a denominator of at most 24 next to it."""
+    from scipy.optimize import linprog
+    rng = np.random.default_rng(5)
+    E, G = 40, 24
+    place = wl.placement_circulant(E, G)
+    place[:3] = 0
+    place[:3, :5] = 1                                  # three hot experts share five ranks
+    load = rng.integers(0, 300, size=E).astype(np.int64)
+    load[:3] += 4000
+    m = sched.lp_optimum_by_flows(load, place)
+    assert 1 <= m.denominator <= G
+    pairs = [(e, g) for e in range(E) for g in range(G) if place[e, g]]
+    nv = len(pairs)
+    c = np.zeros(nv + 1); c[-1] = 1.0
+    A_ub = np.zeros((G, nv + 1)); A_eq = np.zeros((E, nv + 1))
+    for j, (e, g) in enumerate(pairs):
+        A_ub[g, j] = 1.0
+        A_eq[e, j] = 1.0
+    A_ub[:, -1] = -1.0
+    res = linprog(c, A_ub=A_ub, b_ub=np.zeros(G), A_eq=A_eq, b_eq=load.astype(float), bounds=[(0, None)] * (nv + 1),
+                  method="highs")
+    assert res.status == 0
+    assert abs(res.fun - float(m)) < 1e-6 * max(1.0, res.fun)
+    assert m == Fraction(res.fun).limit_denominator(G)
+    assert -(-m.numerator // m.denominator) == sched.min_max_load(load, place)
