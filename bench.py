@@ -405,7 +405,7 @@ def run_placement_search(args, cfg, dev):
     adds = float(n) * G * 2 ** (G - 1)
     b = int(best.cpu()[0])
     line = {
-        "metric": "placement candidates scored per second (Section 5.3 search; score = Eq. 3, or M* beyond 16 ranks)",
+        "metric": "placement candidates scored per second (Section 5.3 search; score = m of Eq. 3)",
         "value": round(n / (ms * 1e-3), 1), "unit": "candidates/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int32", "data": "synthetic",

@@ -213,16 +213,17 @@ int fine_replica_counts(const fine_shape* shape, const int32_t* load, int32_t sl
  * subsets.   place [n,E,G] uint8 (non-zero = replica); load [E] int32 -> m_num [n] int64,
  * m_den [n] int32 out: m as a reduced fraction (0 is 0/1).
  * A placement in which an expert with load has no replica gets m_num = -1, m_den = 0.
- * For more than 16 ranks the subsets cannot be enumerated: the score is then the integer
- * optimum M* = ceil(m) of Eq. 1, found with exact integer flows, as M* / 1 (limit: about
- * 4 E G + 4 G G + 16 E bytes must fit in 64 KB of LDS, else FINE_UNSUPPORTED).
+ * For more than 16 ranks the subsets cannot be enumerated: the same m is found with exact
+ * integer flows (a parametric search over the densities of closed rank sets; limit: about
+ * 4 E G + 4 G G + 16 E bytes must fit in 64 KB of LDS, else FINE_UNSUPPORTED).  Only if the
+ * loads sum to 2^31 / G or more is the integer optimum M* = ceil(m) written instead, as M* / 1.
  */
 int fine_eval_placements(const fine_shape* shape, int32_t n, const uint8_t* place, const int32_t* load,
                          int64_t* m_num, int32_t* m_den, void* stream);
 
 /*
  * Section 5.3, step 2: draw n random placements with the replica counts `counts` and keep the
- * one whose score (m of Eq. 3; M* = ceil(m) for more than 16 ranks, see above) is smallest
+ * one whose score (m of Eq. 3, as fine_eval_placements computes it) is smallest
  * (ties: the lowest candidate index).
  * Candidate c is drawn expert by expert, experts with more replicas first (ties: lower
  * index); an expert's replicas go to the ranks with the most free slots, ties by the larger

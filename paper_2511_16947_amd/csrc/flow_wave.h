@@ -158,9 +158,9 @@ __device__ inline void push_path(const Ctx& c, int len, int amount, int e_cur, i
 }
 
 // Everything on each expert's first replica: fills x, A and the rank loads from the replica masks
-// c.pm and the expert loads (negative reads as 0).  Returns (to every lane) whether some expert with
-// load has no replica.  The arrays must not be in use; ends with a barrier.
-__device__ inline bool start_on_first_replicas(const Ctx& c, const int32_t* __restrict__ load) {
+// c.pm and the expert loads (negative reads as 0) times `scale`.  Returns (to every lane) whether
+// some expert with load has no replica.  The arrays must not be in use; ends with a barrier.
+__device__ inline bool start_on_first_replicas(const Ctx& c, const int32_t* __restrict__ load, int scale = 1) {
     const int l = lane();
     for (int i = l; i < c.G * c.AS; i += kW) c.A[i] = 0;
     for (int i = l; i < c.G; i += kW) c.ld[i] = 0;
@@ -169,7 +169,7 @@ __device__ inline bool start_on_first_replicas(const Ctx& c, const int32_t* __re
     int bad = 0;
     for (int e = l; e < c.E; e += kW) {
         const u64 m = c.pm[e];
-        const int le = max(load[e], 0);
+        const int le = max(load[e], 0) * scale;
         if (m == 0ull) {
             if (le > 0) bad = 1;
         } else if (le > 0) {
@@ -210,6 +210,43 @@ __device__ inline int optimum_value(const Ctx& c, int P) {
         push_path(c, len, amount, -1, 0);
     }
     return M;
+}
+
+// m of Eq. 3, the maximum density over sets of ranks, as a fraction num / den with den <= G (not
+// reduced), for P units in all with P * G < 2^31.  lambda starts at P / G, the density of the set of
+// all ranks, and only ever moves to the density of an actual set, so it never exceeds m.  With every
+// load multiplied by den, "can all loads be placed with rank loads <= lambda" is an integer flow
+// with capacity num per rank.  A search from a rank above capacity that finds no rank below it
+// returns a closed set S: every expert with units in S has all its replicas in S and every other
+// expert has none there, so the units in S are den * load(S), no rank of S is below capacity and one
+// is above: load(S) / |S| > lambda.  lambda moves there and the flow starts again in the new scale.
+// When no rank is above capacity the loads fit under lambda, so m <= lambda, hence m = lambda.
+__device__ inline void exact_density(const Ctx& c, const int32_t* __restrict__ load, int P, int* num_out, int* den_out) {
+    const int l = lane();
+    int num = P, den = c.G;
+    while (true) {
+        start_on_first_replicas(c, load, den);
+        bool moved = false;
+        while (true) {
+            const int mine = (l < c.G) ? c.ld[l] : 0;
+            const u64 over = __ballot(l < c.G && mine > num);
+            if (over == 0ull) break;
+            const int a = __ffsll((long long)over) - 1;
+            u64 visited; int len, cap;
+            const int r = bfs(c, a, (l < c.G) && (mine < num), &visited, &len, &cap);
+            if (r < 0) {
+                const bool in = (l < c.G) && ((visited >> l) & 1ull);
+                num = wave_sum_i(in ? mine : 0) / den;
+                den = __popcll(visited);
+                moved = true;
+                break;
+            }
+            push_path(c, len, min(min(c.ld[a] - num, num - c.ld[r]), cap), -1, 0);
+        }
+        if (!moved) break;
+    }
+    *num_out = num;
+    *den_out = den;
 }
 
 // bytes of LDS behind a Ctx for E experts on G ranks

@@ -9,7 +9,7 @@
 //                      (or the block reads given ones); the block then evaluates Eq. 3 over all
 //                      2^G - 1 rank subsets for one candidate after the other.
 //   k_score_flow       the same for more than 16 ranks, where the subsets cannot be enumerated: one
-//                      wavefront per candidate finds M* = ceil(m) with exact integer flows.
+//                      wavefront per candidate finds the same m with exact integer flows.
 //   k_pick             the candidate with the smallest m (ties: lowest index); draws it again and
 //                      writes it out as a mask [E][G].
 //
@@ -339,8 +339,9 @@ __global__ __launch_bounds__(kScoreThreads) void k_score(const int32_t* __restri
 
 // ---------------------------------------------------------------------------
 // step 2 for more than 16 ranks: 2^G subsets cannot be enumerated.  One wavefront per candidate
-// finds M* = ceil(m) with exact integer flows (flow_wave.h) and reports it as M* / 1: candidates
-// whose m differ by less than one token tie.
+// finds the same m with exact integer flows (flow::exact_density) and writes it as a reduced
+// fraction.  Loads summing to 2^31 / G or more do not fit the scaled flow: then M* = ceil(m) is
+// written as M* / 1.
 // ---------------------------------------------------------------------------
 template <bool DRAW>
 __global__ __launch_bounds__(64) void k_score_flow(const int32_t* __restrict__ load, const int32_t* __restrict__ counts,
@@ -365,13 +366,26 @@ __global__ __launch_bounds__(64) void k_score_flow(const int32_t* __restrict__ l
     }
     __syncthreads();
     const bool bad = flow::start_on_first_replicas(c, load);
-    int P = 0;
-    for (int e = l; e < E; e += 64) P += max(load[e], 0);
-    P = flow::wave_sum_i(P);
-    const int M = bad ? -1 : flow::optimum_value(c, P);
+    long long Pl = 0;
+    for (int e = l; e < E; e += 64) Pl += max(load[e], 0);
+    Pl += __shfl_xor(Pl, 32, 64); Pl += __shfl_xor(Pl, 16, 64); Pl += __shfl_xor(Pl, 8, 64);
+    Pl += __shfl_xor(Pl, 4, 64); Pl += __shfl_xor(Pl, 2, 64); Pl += __shfl_xor(Pl, 1, 64);
+    int num = -1, den = 0;
+    if (!bad) {
+        if (Pl * G < 0x7fffffffll) {
+            flow::exact_density(c, load, (int)Pl, &num, &den);
+            int a = num, b = den;                     // reduce by the greatest common divisor
+            while (b != 0) { const int t = a % b; a = b; b = t; }
+            if (a > 1) { num /= a; den /= a; }
+            if (num == 0) den = 1;
+        } else {
+            num = flow::optimum_value(c, (int)min(Pl, 0x7fffffffll));
+            den = 1;
+        }
+    }
     if (l == 0) {
-        m_num[cand] = M;
-        m_den[cand] = bad ? 0 : 1;
+        m_num[cand] = num;
+        m_den[cand] = den;
     }
 }
 

@@ -22,6 +22,10 @@ def dev_i32(a):
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
 
 
+def dev_u8(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint8)).to(DEV)
+
+
 def gpu_counts(load, E, G, slots):
     counts = torch.empty(E, dtype=torch.int32, device=DEV)
     fm.fine_replica_counts(shape_for(E, G), dev_i32(load), slots, counts)
@@ -70,7 +74,7 @@ SEARCH_CASES = [
     ("tight_g16", 64, 16, 5, "1.2", 65536, 8, 2),
     ("tight_g14", 24, 14, 2, "1.1", 5000, 6, 6),
     ("tight_g13", 20, 13, 2, "1.4", 5000, 6, 5),
-    # more than 16 ranks: scored by M* = ceil(m) through integer flows
+    # more than 16 ranks: the same m through integer flows
     ("flow_g17", 20, 17, 2, "1.2", 3000, 6, 11),
     ("flow_g24", 48, 24, 3, "1.5", 20000, 6, 12),
     ("flow_cfg4_like_g32", 256, 32, 10, "1.0", 32768, 4, 13),
@@ -108,7 +112,7 @@ def test_given_placements_are_scored_by_eq3():
         (wl.placement_circulant(64, 16), wl.zipf_loads(64, 65536, 2.5, 4)),
         (wl.placement_full(16, 4), wl.zipf_loads(16, 1000, 1.5, 5)),
         (wl.placement_home(32, 8), wl.zipf_loads(32, 1024, 1.0, 6)),
-        (wl.placement_circulant(256, 32), wl.zipf_loads(256, 32768, 1.0, 7)),       # 32 ranks: M* through flows
+        (wl.placement_circulant(256, 32), wl.zipf_loads(256, 32768, 1.0, 7)),       # 32 ranks: m through flows
         (wl.placement_circulant(64, 32), wl.zipf_loads(64, 4096, 1.6, 8)),
     ]
     for place, load in cases:
@@ -128,6 +132,30 @@ def test_given_placements_are_scored_by_eq3():
         for c in range(n):
             want = placement.max_density(load, stack[c])
             assert (int(m_num[c]), int(m_den[c])) == (want.numerator, want.denominator), (E, G, c)
+
+
+def test_beyond_16_ranks_the_score_is_a_fraction_and_huge_loads_fall_back_to_the_integer_optimum():
+    """Three hot experts share five of 24 ranks: m is their load over 5, a proper fraction, found by
+    flows.  Loads summing to 2^31 / G or more do not fit the scaled flow: M* = ceil(m) comes back."""
+    rng = np.random.default_rng(5)
+    E, G = 40, 24
+    place = wl.placement_circulant(E, G)
+    place[:3] = 0
+    place[:3, :5] = 1
+    load = rng.integers(0, 300, size=E).astype(np.int64)
+    load[:3] += 4002
+    m_num = torch.empty(1, dtype=torch.int64, device=DEV)
+    m_den = torch.empty(1, dtype=torch.int32, device=DEV)
+    fm.fine_eval_placements(shape_for(E, G), 1, dev_u8(place[None]), dev_i32(load), m_num, m_den)
+    torch.cuda.synchronize()
+    want = placement.max_density(load, place)
+    assert want.denominator == 5
+    assert (int(m_num[0]), int(m_den[0])) == (want.numerator, want.denominator)
+    huge = load * 30000                                 # sums to about 5e8: times 24 ranks it passes 2^31
+    assert int(huge.sum()) * G >= 2**31 and int(huge.max()) < 2**31
+    fm.fine_eval_placements(shape_for(E, G), 1, dev_u8(place[None]), dev_i32(huge), m_num, m_den)
+    torch.cuda.synchronize()
+    assert (int(m_num[0]), int(m_den[0])) == (sched.min_max_load(huge, place), 1)
 
 
 def test_expert_with_load_and_no_replica_is_flagged():
