@@ -50,7 +50,7 @@ enum { FINE_F32 = 0, FINE_BF16 = 1 };
 
 /* flags */
 enum {
-    FINE_FLAG_LOCALITY = 1,      /* run the local pass of Algorithm 1 (lines 4-9) first */
+    FINE_FLAG_LOCALITY = 1,      /* run the local pass of Algorithm 1 first: a rank keeps its own tokens up to its replica load */
     FINE_FLAG_SIMPLE_FFN = 2,    /* debugging: plain tiled FMA kernels instead of MFMA */
     FINE_FLAG_ONLY_GEMM1 = 4,    /* measurement: fine_grouped_ffn runs only X[Wg|Wu] + SwiGLU   */
     FINE_FLAG_ONLY_GEMM2 = 8,    /* measurement: fine_grouped_ffn runs only H Wd (H from ws)     */
