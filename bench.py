@@ -262,14 +262,15 @@ def main():
                     "avg_launch_ms": round(dur_ms, 4), "flops_per_launch": flops_per_launch}
 
     es = 4 if cfg.dtype == "f32" else 2
-    gbs = {
-        "permute_GBs": round((2.0 * s.P * s.d * es + 4.0 * s.P) / (stage_ms["permute"] * 1e-3) / 1e9, 1),
-        "combine_GBs": round((s.P * s.d * es + 8.0 * s.P + s.T * s.d * es) / (stage_ms["combine"] * 1e-3) / 1e9, 1),
-        "topk_GBs": round((s.T * s.d * es + s.d * s.E * es + 8.0 * s.P) / (stage_ms["topk"] * 1e-3) / 1e9, 1),
-    }
     ffn_ms_total = float(np.sum(rank_ms))
     detail = {
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        # the HBM-bound stages: algorithmic bytes of the stage / its time, against 8 TB/s
+        "stage_hbm": {k: {"GB": round(b / 1e9, 4), "TBps": round(b / (stage_ms[k] * 1e-3) / 1e12, 3),
+                          "frac_of_8TBps": round(b / (stage_ms[k] * 1e-3) / 8e12, 3)}
+                      for k, b in (("topk", s.T * s.d * es + s.d * s.E * es + 8 * s.P),
+                                   ("permute", 2 * s.P * s.d * es + 4 * s.P),
+                                   ("combine", s.P * s.d * es + 8 * s.P + s.T * s.d * es)) if k in stage_ms},
         "ffn_TFLOPs_per_rank_calls": round(fwd_flop / (ffn_ms_total * 1e-3) / 1e12, 2),
         "layer_TFLOPs_sched_permute_ffn_combine": round(
             fwd_flop / ((stage_ms["sched"] + stage_ms["permute"] + stage_ms["ffn"] + stage_ms["combine"]) * 1e-3) / 1e12, 2),
@@ -280,7 +281,6 @@ def main():
             np.add.reduceat(load, np.arange(0, s.E, max(1, s.E // s.G)))[:s.G].max() / (s.P / s.G)), 3) if s.E >= s.G else None,
         "rank_ffn_ms": [round(v, 4) for v in rank_ms],
         "input_gen_s": round(t_gen, 2),
-        **gbs,
     }
 
     # ---- the same per-rank calls under a restricted placement built from the loads (2 or so replica
