@@ -70,7 +70,6 @@ struct SchedWs {
     size_t inpre;      // int32  [E][G]    pairs of expert e on source ranks < g
     size_t Y;          // int32  [E][G][G] Algorithm 1 transfer table
     size_t Ypre;       // int32  [E][G][G] Ypre[e][g][h] = sum_{g'<g} Y[e][g'][h]
-    size_t solver;     // int32  scratch of the general-placement solver
     size_t total;
     int W;
 };

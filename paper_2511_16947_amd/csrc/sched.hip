@@ -229,7 +229,6 @@ SchedWs sched_ws_layout(const fine_shape& s) {
     w.inpre = o;  o = align_up(o + (size_t)s.E * s.G * 4, 256);
     w.Y = o;      o = align_up(o + (size_t)s.E * s.G * s.G * 4, 256);
     w.Ypre = o;   o = align_up(o + (size_t)s.E * s.G * s.G * 4, 256);
-    w.solver = o; o = align_up(o + (size_t)(s.E * s.G + 4 * (s.E + s.G) + 64) * 4, 256);
     w.total = o;
     return w;
 }
