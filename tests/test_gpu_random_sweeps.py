@@ -1,0 +1,82 @@
+"""Randomised GPU parity sweeps: many small scheduler and placement-scoring instances with shapes
+the hand-picked cases do not list (odd rank counts up to 64, experts with one to six replicas or all
+of them, clustered replicas, loads of zero), each compared bit for bit with the oracle.  Seeds are
+fixed; the same sweeps run for minutes with other seeds are how the solver's rewrites were checked."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2511_16947_amd as fm
+import workloads as wl
+from oracle import placement
+from gpu_common import check_schedule_against_oracle
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_random_restricted_schedules_cold_and_warm(seed):
+    rng = np.random.default_rng(seed)
+    for n in range(40):
+        G = int(rng.choice([2, 3, 4, 5, 8, 12, 16, 17, 24, 32, 48, 64]))
+        E = int(rng.integers(1, 70))
+        K = int(rng.integers(1, min(E, 4) + 1))
+        T = G * int(rng.integers(1, 40))
+        place = np.zeros((E, G), dtype=np.uint8)
+        style = int(rng.integers(0, 4))
+        for e in range(E):
+            c = 1 if style == 0 and rng.random() < 0.7 else int(rng.integers(1, min(G, 6) + 1))
+            if style == 3 and rng.random() < 0.2:
+                c = G
+            place[e, rng.choice(G, size=c, replace=False)] = 1
+        idx = wl.random_topk(T, E, K, seed=int(rng.integers(1 << 30)), skew=float(rng.choice([0.0, 1.0, 2.5])))
+        locality = bool(rng.random() < 0.7)
+        shape = fm.Shape(T, 64, 64, E, K, G, fm.FINE_BF16, fm.FLAG_LOCALITY if locality else 0)
+        sb = fm.SchedBuffers(shape, DEV)
+        idx_d, place_d = torch.from_numpy(idx).to(DEV), torch.from_numpy(place).to(DEV)
+        print("sweep", seed, "case", n, "E", E, "G", G, "K", K, "T", T, "style", style, flush=True)
+        sb.run(shape, idx_d, place_d)
+        torch.cuda.synchronize()
+        check_schedule_against_oracle(sb, idx, E, G, place, locality)
+        prev = torch.from_numpy(rng.integers(-50, 500, (E, G)).astype(np.int32)).to(DEV)
+        fm.fine_sched_warm(shape, idx_d, place_d, prev, sb.load, sb.input_eg, sb.x_eg, sb.max_load, sb.pair_dst,
+                           sb.row_of_pair, sb.pair_of_row, sb.seg_off, sb.rank_off, sb.ws)
+        torch.cuda.synchronize()
+        check_schedule_against_oracle(sb, idx, E, G, place, locality)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_placement_scores(seed):
+    rng = np.random.default_rng(seed)
+    fractional = 0
+    for n in range(30):
+        G = int(rng.choice([2, 3, 5, 8, 11, 12, 13, 14, 17, 18, 24, 31, 32, 40, 64]))
+        E = int(rng.integers(1, 90))
+        nc = 4
+        places = np.zeros((nc, E, G), dtype=np.uint8)
+        for c in range(nc):
+            for e in range(E):
+                k = int(rng.integers(1, min(G, 5) + 1))
+                if rng.random() < 0.3:          # replicas inside a small group of ranks
+                    grp = rng.choice(G, size=min(G, 6), replace=False)
+                    places[c, e, rng.choice(grp, size=min(k, len(grp)), replace=False)] = 1
+                else:
+                    places[c, e, rng.choice(G, size=k, replace=False)] = 1
+        load = (rng.pareto(1.1, size=E) * rng.choice([5, 50, 500])).astype(np.int64)
+        load[rng.random(E) < 0.15] = 0
+        load = np.minimum(load, 1_000_000)
+        if int(load.sum()) * G >= 2**31:
+            continue
+        shape = fm.Shape(G, 64, 64, E, 1, G, fm.FINE_BF16, 0)
+        m_num = torch.empty(nc, dtype=torch.int64, device=DEV)
+        m_den = torch.empty(nc, dtype=torch.int32, device=DEV)
+        print("sweep", seed, "case", n, "E", E, "G", G, flush=True)
+        fm.fine_eval_placements(shape, nc, torch.from_numpy(places).to(DEV),
+                                torch.from_numpy(load.astype(np.int32)).to(DEV), m_num, m_den)
+        torch.cuda.synchronize()
+        for c in range(nc):
+            want = placement.max_density(load, places[c])
+            assert (int(m_num[c]), int(m_den[c])) == (want.numerator, want.denominator), (n, c, E, G)
+            fractional += want.denominator > 1
+    assert fractional > 10
