@@ -80,3 +80,76 @@ def test_random_placement_scores(seed):
             assert (int(m_num[c]), int(m_den[c])) == (want.numerator, want.denominator), (n, c, E, G)
             fractional += want.denominator > 1
     assert fractional > 10
+
+
+def _random_placement(rng, E, G):
+    place = np.zeros((E, G), dtype=np.uint8)
+    for e in range(E):
+        place[e, rng.choice(G, size=int(rng.integers(1, G + 1)), replace=False)] = 1
+    return place
+
+
+def test_random_layers_forward():
+    """Random bf16 layer shapes (d, f multiples of 64; one to 136 experts; every tile kind; restricted
+    placements; per-rank or all-ranks calls): router parity, bit-exact schedule, output within tolerance."""
+    from oracle import moe
+    from gpu_common import GpuLayer, check_router, max_rel_err, to64, tol_for, weights_of_factory
+    rng = np.random.default_rng(11)
+    for n in range(16):
+        G = int(rng.choice([1, 2, 3, 4, 8]))
+        E = int(rng.choice([1, 2, 3, 5, 8, 16, 24, 40, 72, 136]))
+        K = int(rng.integers(1, min(E, 4) + 1))
+        T = G * int(rng.integers(1, 300))
+        d, f = 64 * int(rng.integers(1, 9)), 64 * int(rng.integers(1, 12))
+        if n % 5 == 4:
+            f = 64 * int(rng.integers(40, 90))          # a long k range in GEMM 2
+        tile = int(rng.integers(0, 4))
+        cfg = wl.LayerConfig("sweep", T, d, f, E, K, G, "bf16", int(rng.integers(1, 1000)), "scaled_z",
+                             float(rng.choice([0.5, 1.5, 3.0])))
+        print("layer", n, "T", T, "d", d, "f", f, "E", E, "K", K, "G", G, "tile", tile, flush=True)
+        inp = wl.make_inputs(cfg, DEV)
+        layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+        place = _random_placement(rng, E, G) if G > 1 and n % 2 else None
+        layer.forward(place=None if place is None else torch.from_numpy(place).to(DEV), per_rank=bool(n % 3))
+        check_router(cfg, inp, layer.topk_idx, layer.topk_w)
+        idx = layer.topk_idx.cpu().numpy()
+        check_schedule_against_oracle(layer.sb, idx, E, G, place)
+        ref = moe.dense_reference_by_expert(to64(inp.x), idx, to64(layer.topk_w), weights_of_factory(inp))
+        assert max_rel_err(to64(layer.out), ref) <= tol_for(cfg), n
+
+
+def test_random_layers_backward():
+    from oracle import moe
+    from gpu_common import GpuLayer, max_rel_err, to64, weights_of_factory
+    from test_gpu_backward import GpuBackward, TOL
+    rng = np.random.default_rng(12)
+    c5 = wl.CONFIGS["cfg5_train"]
+    for n in range(12):
+        G = int(rng.choice([1, 2, 4, 8]))
+        E = int(rng.choice([1, 2, 4, 8, 16, 24, 40]))
+        K = int(rng.integers(1, min(E, 4) + 1))
+        T = G * int(rng.integers(1, 200))
+        d, f = 64 * int(rng.integers(1, 7)), 64 * int(rng.integers(1, 9))
+        tile = int(rng.integers(0, 4))
+        cfg = wl.scaled(c5, name="sweep", T=T, d=d, f=f, E=E, K=K, G=G, seed=int(rng.integers(1, 1000)),
+                        bias_kind="scaled_z", bias_scale=float(rng.choice([0.5, 2.0])))
+        print("backward", n, "T", T, "d", d, "f", f, "E", E, "K", K, "G", G, "tile", tile, flush=True)
+        inp = wl.make_inputs(cfg, DEV)
+        layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+        if n % 2:
+            layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+        place = _random_placement(rng, E, G) if G > 1 and n % 3 == 0 else None
+        layer.forward(place=None if place is None else torch.from_numpy(place).to(DEV))
+        bwd = GpuBackward(layer)
+        bwd.run()
+        idx = layer.topk_idx.cpu().numpy()
+        check_schedule_against_oracle(layer.sb, idx, E, G, place)
+        g = moe.backward_dense(to64(inp.x), idx, to64(layer.topk_w), weights_of_factory(inp), to64(inp.d_out))
+        assert max_rel_err(to64(bwd.d_x), g["d_x"]) <= TOL, n
+        assert max_rel_err(to64(bwd.d_topk_w), g["d_topk_w"]) <= TOL, n
+        for e in range(E):
+            for got, key in ((bwd.d_wg, "d_w_gate"), (bwd.d_wu, "d_w_up"), (bwd.d_wd, "d_w_down")):
+                if e in g[key]:
+                    assert max_rel_err(to64(got[e]), g[key][e]) <= TOL, (n, key, e)
+                else:
+                    assert not got[e].any(), (n, key, e)
