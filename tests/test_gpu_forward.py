@@ -223,6 +223,41 @@ def test_bad_arguments_return_errors():
     assert ei.value.code == fm.FINE_WORKSPACE_TOO_SMALL
 
 
+def test_a_step_with_the_split_gate_can_be_captured_in_a_graph():
+    """128 experts and 512 tokens: the gate runs as two kernels (blocks share token tiles over parts of
+    k, partial logits in the workspace, then the selection).  Captured and replayed with eager work in
+    between, every replay must give the eager bits."""
+    cfg = wl.LayerConfig("graph_split_gate", 512, 1024, 128, 128, 4, 4, "bf16", 13, "scaled_z", 1.0)
+    assert fm.fine_workspace_bytes(fm.shape_of(cfg), fm.WS_TOPK) > 256
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY)
+    layer.forward(per_rank=True)
+    want_idx, want_w, want_out = layer.topk_idx.clone(), layer.topk_w.clone(), layer.out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            layer.topk()
+            layer.sched()
+            layer.permute()
+            for r in range(cfg.G):
+                layer.ffn(r)
+            layer.combine()
+    torch.cuda.current_stream().wait_stream(side)
+    for i in range(3):
+        layer.out.zero_()
+        layer.topk_idx.fill_(-1)
+        layer.ws_topk.fill_(0x7f)                           # stale partial logits must not matter
+        layer.permute()                                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(layer.topk_idx, want_idx), i
+        assert torch.equal(layer.topk_w, want_w), i
+        assert torch.equal(layer.out.view(torch.int16), want_out.view(torch.int16)), i
+
+
 @pytest.mark.parametrize("restricted", [False, True])
 def test_a_step_can_be_captured_in_a_graph(restricted):
     """The library allocates nothing, synchronises nothing and clears its own counters in kernels,
