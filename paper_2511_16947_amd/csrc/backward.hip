@@ -36,7 +36,8 @@ __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, con
         if constexpr (W8) {
             const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
             RowDmaOperand<WM> oa;
-            oa.init(dy + (size_t)te.row0 * d, [&](int r) { return (size_t)min(r, te.rows - 1) * d; },
+            // rows past the tile's last lie beyond the descriptor's size: zeros by DMA, no memory request
+            oa.init(dy + (size_t)te.row0 * d, [&](int r) { return (size_t)r * d; },
                     (uint32_t)((size_t)te.rows * d * 2), (wave / WAVES_N) * WM * 32);
             RowDmaOperand<WN> ob;
             ob.init(W, [&](int n) { return (size_t)min(n0 + n, f - 1) * d; }, (uint32_t)((size_t)f * d * 2),
@@ -154,7 +155,7 @@ __device__ __forceinline__ void bwd_dx_body(const uint16_t* __restrict__ dact, c
         if constexpr (W8) {
             const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
             RowDmaOperand<WM> oa;
-            oa.init(dact + (size_t)te.row0 * (2 * f), [&](int r) { return (size_t)min(r, te.rows - 1) * (2 * f); },
+            oa.init(dact + (size_t)te.row0 * (2 * f), [&](int r) { return (size_t)r * (2 * f); },
                     (uint32_t)((size_t)te.rows * 2 * f * 2), (wave / WAVES_N) * WM * 32);
             RowDmaOperand<WN> ob;
             ob.init(Wg, [&](int n) { return (size_t)min(n0 + n, d - 1) * f; }, (uint32_t)((size_t)d * f * 2),

@@ -54,7 +54,10 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
         if constexpr (W8) {
             const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
             RowDmaOperand<WM, BM> oa;
-            oa.init(A + (size_t)te.row0 * lda, a_row, (uint32_t)((size_t)te.rows * lda * 2), (wave / WAVES_N) * WM * 32);
+            // rows past the tile's last lie beyond the descriptor's size: the DMA writes zeros for them
+            // and asks memory for nothing (their results are never stored)
+            oa.init(A + (size_t)te.row0 * lda, [&](int r) { return (size_t)r * lda; },
+                    (uint32_t)((size_t)te.rows * lda * 2), (wave / WAVES_N) * WM * 32);
             DmaOperand<WN> ob;
             const int wn = wave % WAVES_N;
             if constexpr (EPI == 0) {
