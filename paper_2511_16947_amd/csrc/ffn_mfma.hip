@@ -128,7 +128,8 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     // [b * per, (b+1) * per) of that sequence.  A block that computes only part of a tile's k
     // range writes its accumulators to its slot (two per block: a range begins and ends inside
     // at most one tile each) and counts itself in; whoever counts in last adds the parts up in
-    // block order - the same sum whoever it is - and runs the epilogue.  Nobody waits.
+    // block order - the same sum whoever it is - and runs the epilogue.  Nobody waits.  (A rest too
+    // small for that to pay is cut into few parts instead, see below.)
     __shared__ int s_last;
     const int nblk = gridDim.x, bid = xcd_contiguous_id();
     // the cut pays when the k-steps it saves (the last round would take nk, the cut takes
@@ -138,11 +139,20 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     // workloads stream weights from HBM, the cut only pays for long k ranges (32 steps).
     const int whole_rounds = (total / nblk) * nblk;
     const bool cut = W8 && (long long)nk * (nblk - (total - whole_rounds)) > (long long)(WM == 4 ? 16 : 32) * nblk;
-    const int full = cut ? whole_rounds : total;
+    // Below that break-even a small rest would still cost a whole extra round (24 of 280 tiles of 32
+    // steps: one more tile time with 232 CUs idle).  Spreading so few steps over the whole grid would
+    // leave each tile in ten parts for its last block to add up; instead every rest tile is cut into 2
+    // or 4 parts of at least 8 steps, part p of rest tile t going to block t + p * rest ("few parts").
+    const int rest_if = total - whole_rounds;
+    int few = 0;
+    if (W8 && !cut && rest_if > 0)
+        for (int p = 4; p >= 2 && few == 0; p >>= 1)
+            if (rest_if * p <= nblk && nk % p == 0 && nk / p >= 8) few = p;
+    const int full = (cut || few) ? whole_rounds : total;
     const int rest = total - full;
     const int per = (rest * nk + nblk - 1) / nblk;
     int32_t* counters = count + kSkCounterOffset;
-    auto slot_of = [&](int blk, int t) { return blk * 2 + (((blk * per) / nk) == t ? 0 : 1); };
+    auto slot_of = [&](int blk, int t) { return few ? blk * 2 : blk * 2 + (((blk * per) / nk) == t ? 0 : 1); };
     // Partial sums travel as 16-byte buffer stores and loads with the sc0 sc1 cache policy: they
     // are written through and read past the per-XCD L2 one by one, so no cache-wide write-back or
     // invalidate (a fence) is needed, which would cost every block on the XCD its cached operand
@@ -160,11 +170,18 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
 #endif
     int next_whole = bid, u = bid * per;
     const int u1 = min(rest * nk, u + per);
+    bool part_taken = false;
     for (;;) {
         int work, kb = 0, kn = nk;
         if (next_whole < full) {
             work = next_whole;
             next_whole += nblk;
+        } else if (W8 && few) {
+            if (part_taken || bid >= rest * few) break;
+            part_taken = true;
+            kn = nk / few;
+            kb = (bid / rest) * kn;
+            work = full + bid % rest;
         } else if (W8 && u < u1) {
             const int t = u / nk;
             kb = u - t * nk;
@@ -183,7 +200,10 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
         if constexpr (W8) {
             if (kn != nk) {
                 const int t = work - full;
-                const int first = (t * nk) / per, last = (t * nk + nk - 1) / per;
+                // the blocks that hold parts of tile t: first, first + step, ... (n_parts of them)
+                const int first = few ? t : (t * nk) / per;
+                const int step = few ? rest : 1;
+                const int n_parts = few ? few : (t * nk + nk - 1) / per - first + 1;
                 const int mine = slot_of(bid, t);
                 static_for<WM * WN>([&](auto m) {
                     static_for<4>([&](auto q) {
@@ -198,13 +218,13 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                 __syncthreads();
                 if (threadIdx.x == 0)
                     s_last = __hip_atomic_fetch_add(&counters[t], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                             last - first;
+                             n_parts - 1;
                 __syncthreads();
                 finish = s_last != 0;
                 if (finish) {
                     zero_acc<WM, WN>(acc);
-                    for (int blk = first; blk <= last; ++blk) {
-                        const int sl = slot_of(blk, t);
+                    for (int i = 0; i < n_parts; ++i) {
+                        const int sl = slot_of(first + i * step, t);
                         static_for<WM * WN / 2>([&](auto mp) {
                             u32x4 v[8];
                             static_for<8>([&](auto g) {
