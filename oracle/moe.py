@@ -99,7 +99,7 @@ def combine(y_perm, row_of_pair, topk_w):
 # gradients of the dense definition (the router is not differentiated)
 # --------------------------------------------------------------------------
 
-def backward_dense(x, topk_idx, topk_w, weights_of, d_out, want_weight_grads=True):
+def backward_dense(x, topk_idx, topk_w, weights_of, d_out, want_weight_grads=True, weight_grad_experts=None):
     """Closed-form gradients of L = sum(out * d_out) for the dense definition.
 
     With a = v Wg, b = v Wu, s = sigmoid(a), h = a s b, y = h Wd:
@@ -107,7 +107,8 @@ def backward_dense(x, topk_idx, topk_w, weights_of, d_out, want_weight_grads=Tru
       dv = da Wg^T + db Wu^T;  dWg = v^T da;  dWu = v^T db;  dWd = h^T dy,
     where dy = topk_w[t,k] * d_out[t] for the pair (t,k), and
       d topk_w[t,k] = <d_out[t], FFN_e(x[t])>.
-    Returns dict(d_x, d_topk_w, d_w_gate{e}, d_w_up{e}, d_w_down{e})."""
+    Returns dict(d_x, d_topk_w, d_w_gate{e}, d_w_up{e}, d_w_down{e}); weight_grad_experts
+    (a collection of expert indices) limits which experts' weight gradients are kept."""
     x = np.asarray(x, dtype=np.float64)
     d_out = np.asarray(d_out, dtype=np.float64)
     topk_w = np.asarray(topk_w, dtype=np.float64)
@@ -131,7 +132,7 @@ def backward_dense(x, topk_idx, topk_w, weights_of, d_out, want_weight_grads=Tru
         da = dh * b * s * (1.0 + a * (1.0 - s))
         db = dh * a * s
         np.add.at(d_x, tt, da @ Wg.T + db @ Wu.T)
-        if want_weight_grads:
+        if want_weight_grads and (weight_grad_experts is None or int(e) in weight_grad_experts):
             gWg[int(e)] = v.T @ da
             gWu[int(e)] = v.T @ db
             gWd[int(e)] = h.T @ dy

@@ -20,6 +20,18 @@ def max_rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return float(np.abs(got - want).max() / denom)
 
 
+def max_rel_err_rows(got: np.ndarray, want: np.ndarray) -> float:
+    """The same measure taken row by row, max |got[r] - want[r]| / max |want[r]|, and the
+    largest of them: a wrong row cannot hide behind a larger one elsewhere in the tensor.
+    Rows of zeros must be zeros."""
+    denom = np.abs(want).max(axis=1)
+    err = np.abs(got - want).max(axis=1)
+    zero = denom == 0.0
+    if zero.any() and err[zero].max() > 0.0:
+        return float("inf")
+    return float((err[~zero] / denom[~zero]).max()) if (~zero).any() else 0.0
+
+
 def tol_for(cfg) -> float:
     return 1e-5 if cfg.dtype == "f32" else 2e-2
 

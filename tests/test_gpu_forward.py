@@ -6,7 +6,7 @@ import torch
 import paper_2511_16947_amd as fm
 import workloads as wl
 from oracle import moe, router, sched
-from gpu_common import (GpuLayer, check_router, check_schedule_against_oracle, max_rel_err, to64, tol_for,
+from gpu_common import (GpuLayer, check_router, check_schedule_against_oracle, max_rel_err, max_rel_err_rows, to64, tol_for,
                         weights_of_factory)
 
 pytestmark = pytest.mark.gpu
@@ -180,6 +180,43 @@ def test_tiles_cut_along_k(tile):
     weights_of = weights_of_factory(inp)
     ref_y = moe.grouped_ffn(moe.permute(to64(inp.x), want["pair_of_row"], cfg.K), want["seg_off"], weights_of)
     assert max_rel_err(to64(layer.y_perm), ref_y) <= tol_for(cfg)
+    first = layer.y_perm.clone()
+    for _ in range(3):
+        layer.y_perm.zero_()
+        layer.ffn(-1)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.y_perm, first)
+
+
+@pytest.mark.parametrize("tile,d,f,T,parts", [(3, 1024, 1024, 256, 2), (3, 1024, 1024, 250, 2),
+                                              (2, 2048, 2048, 256, 4), (2, 2048, 2048, 232, 4)])
+def test_a_small_rest_of_tiles_is_cut_into_few_parts(tile, d, f, T, parts):
+    """Fewer tiles than blocks and a k range too short for the cut over the whole grid (16 k-tiles
+    on the 256-row tile, 32 on the 128-row tile): every tile of the rest is cut into `parts` parts,
+    part p of tile t on block t + p * rest, in both GEMMs.  Every element and every row against
+    the oracle, whole and ragged row tiles, and bit-stable from run to run."""
+    cfg = wl.LayerConfig("few_parts", T, d, f, 2, 2, 1, "bf16", 11, "scaled_z", 0.5)
+    # both GEMMs take the branch: rest tiles * parts fit the grid of 256 blocks, parts divide the
+    # k-tiles, at least 8 k-tiles per part, and the whole-grid cut does not pay
+    bm = 256 if tile == 3 else 128
+    for kd, n_out, bnc in ((d, f, 128), (f, d, 256)):
+        nk, rest = kd // 64, 2 * -(-T // bm) * (n_out // bnc)
+        assert rest * parts <= 256 and nk % parts == 0 and nk // parts >= 8 and (parts == 4 or rest * 4 > 256 or nk // 4 < 8)
+        assert nk * (256 - rest) <= (16 if tile == 3 else 32) * 256
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+    print("few-parts case tile", tile, "T", T, flush=True)
+    layer.y_perm.fill_(float("nan"))
+    layer.forward()
+    idx = layer.topk_idx.cpu().numpy()
+    want = check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G)
+    weights_of = weights_of_factory(inp)
+    ref_y = moe.grouped_ffn(moe.permute(to64(inp.x), want["pair_of_row"], cfg.K), want["seg_off"], weights_of)
+    got = to64(layer.y_perm)
+    assert max_rel_err(got, ref_y) <= tol_for(cfg)
+    assert max_rel_err_rows(got, ref_y) <= tol_for(cfg)
+    ref_out = moe.combine(ref_y, want["row_of_pair"], to64(layer.topk_w))
+    assert max_rel_err_rows(to64(layer.out), ref_out) <= tol_for(cfg)
     first = layer.y_perm.clone()
     for _ in range(3):
         layer.y_perm.zero_()
