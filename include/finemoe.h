@@ -115,8 +115,9 @@ int fine_topk(const fine_shape* shape, const void* x, const void* w_router, cons
  * sequence into chunks of M* = ceil(P/G)); with a placement the optimum is found by
  * exact integer augmenting paths on the device (limit: E*G*4 + E*8 + G*G*4 bytes must fit
  * in 160 KB of LDS, else FINE_UNSUPPORTED).  The host cannot read `place`: if an expert with
- * load has an empty row of `place` no schedule exists; then max_load[0] = -1, x_eg = 0 and
- * pair_dst = row_of_pair = -1 for every pair (pair_of_row is left untouched).
+ * load has an empty row of `place` no schedule exists; then max_load[0] = -1, x_eg = 0,
+ * seg_off = rank_off = 0, pair_dst = -1 for every pair and row_of_pair = pair_of_row = the
+ * identity, so that later calls on these outputs compute nothing and stay inside their buffers.
  */
 int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
                int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
@@ -173,10 +174,10 @@ int fine_combine(const fine_shape* shape, const void* y_perm, const int32_t* row
                  const float* topk_w, void* out, void* stream);
 
 /*
- * Backward of permute + expert computation + combine for all ranks (rank must be -1;
- * other values return FINE_UNSUPPORTED), FINE_BF16 only.  The paper aggregates the
- * gradients of an expert's replicas with a data-parallel all-reduce (Section 2.2); on one
- * GPU the replicas share one fp32 accumulator per expert, summed in ascending rank order.
+ * Backward of permute + expert computation + combine, FINE_BF16 only, for all ranks (rank == -1)
+ * or for one rank's rows (0 <= rank < G).  The paper aggregates the gradients of an expert's
+ * replicas with a data-parallel all-reduce (Section 2.2); on one GPU the replicas share one fp32
+ * accumulator per expert, summed in ascending rank order.
  *   d_out [T,d] dtype; x_perm, y_perm [P,d] as produced by the forward entry points;
  *   act_save [P,2f] as written by fine_grouped_ffn, or NULL (then recomputed into ws);
  *   d_x [T,d] dtype out: d_x[t] = sum_k dXp[row_of_pair[t*K+k]];
@@ -184,6 +185,12 @@ int fine_combine(const fine_shape* shape, const void* y_perm, const int32_t* row
  *        not differentiated);
  *   d_w_gate, d_w_up [E,d,f] fp32, d_w_down [E,f,d] fp32: accumulate != 0 adds to the
  *        buffers, accumulate == 0 overwrites them (experts without rows get zeros).
+ * One rank at a time: the calls for ranks 0, 1, ..., G-1 must be made in this order on one stream
+ * with the same `ws`, which carries the rows' gradients from call to call.  The call for rank r
+ * writes d_topk_w of the pairs it computes and adds (accumulate != 0) or writes (accumulate == 0:
+ * zeros for experts without rows on rank r) the weight gradients of its own rows, so rank 0 with
+ * accumulate = 0 and the others with accumulate = 1 give the sums of the all-ranks call up to
+ * fp32 summation order; d_x is written by the call for rank G-1, bit-equal to the all-ranks call.
  */
 int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
                   const void* x_perm, const void* y_perm, const void* act_save,

@@ -145,13 +145,14 @@ int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
     if (!d_out || !x_perm || !y_perm || !w_gate || !w_up || !w_down || !row_of_pair || !pair_of_row || !seg_off ||
         !topk_w || !d_x || !d_topk_w || !d_w_gate || !d_w_up || !d_w_down || !ws)
         return FINE_INVALID_ARG;
-    if (rank != -1) return FINE_UNSUPPORTED;
+    if (rank < -1 || rank >= shape->G) return FINE_INVALID_ARG;
     if (!aligned16(d_out) || !aligned16(x_perm) || !aligned16(y_perm) || !aligned16(w_gate) || !aligned16(w_up) ||
         !aligned16(w_down) || !aligned16(d_x) || !aligned16(d_w_gate) || !aligned16(d_w_up) || !aligned16(d_w_down) ||
         !aligned16(ws) || (act_save && !aligned16(act_save)))
         return FINE_INVALID_ARG;
     if (ws_bytes < bwd_ws_layout(*shape).total) return FINE_WORKSPACE_TOO_SMALL;
-    return launch_backward(*shape, d_out, x_perm, y_perm, act_save, w_gate, w_up, w_down, row_of_pair, pair_of_row,
+    const int lo = rank < 0 ? 0 : rank, hi = rank < 0 ? shape->G : rank + 1;
+    return launch_backward(*shape, lo, hi, d_out, x_perm, y_perm, act_save, w_gate, w_up, w_down, row_of_pair, pair_of_row,
                            seg_off, topk_w, d_x, d_topk_w, d_w_gate, d_w_up, d_w_down, accumulate, (char*)ws,
                            (hipStream_t)stream);
 }

@@ -200,7 +200,8 @@ struct WgradProblem {
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, WgradProblem p2,
-                                           const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
+                                           const int32_t* __restrict__ seg_off, int E, int g_lo, int g_hi,
+                                           int accumulate) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -218,11 +219,12 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
         else if (j >= t0) { p = p1; j -= t0; }
         const int ntm = cdiv_dev(p.M, BM);
         const int m0 = (j % ntm) * BM, n0 = (j / ntm) * BN;
-        // k-tiles: 64 rows at a time through the expert's segment on every rank, ascending
+        // k-tiles: 64 rows at a time through the expert's segment on every rank of [g_lo, g_hi), ascending
         int nk = 0;
-        for (int g = 0; g < G; ++g)
+        for (int g = g_lo; g < g_hi; ++g)
             nk += (seg_off[(size_t)g * (E + 1) + e + 1] - seg_off[(size_t)g * (E + 1) + e] + BK - 1) / BK;
-        int cur_g = -1, cur_k = 0, cur_lo = 0, cur_hi = 0;
+        if (nk == 0 && accumulate) continue;      // nothing to add (block-uniform)
+        int cur_g = g_lo - 1, cur_k = 0, cur_lo = 0, cur_hi = 0;
         auto k_tile = [&](int) {
             while (cur_k >= cur_hi) {          // advance to the next non-empty segment
                 ++cur_g;
@@ -269,32 +271,31 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 __global__ __launch_bounds__(256) void k_wgrad(WgradProblem p0, WgradProblem p1, WgradProblem p2,
-                                               const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
-    wgrad_body<WAVES_M, WAVES_N, WM, WN>(p0, p1, p2, seg_off, E, G, accumulate);
+                                               const int32_t* __restrict__ seg_off, int E, int g_lo, int g_hi,
+                                               int accumulate) {
+    wgrad_body<WAVES_M, WAVES_N, WM, WN>(p0, p1, p2, seg_off, E, g_lo, g_hi, accumulate);
 }
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 __global__ __launch_bounds__(512) void k_wgrad_w8(WgradProblem p0, WgradProblem p1, WgradProblem p2,
-                                                  const int32_t* __restrict__ seg_off, int E, int G, int accumulate) {
-    wgrad_body<WAVES_M, WAVES_N, WM, WN>(p0, p1, p2, seg_off, E, G, accumulate);
+                                                  const int32_t* __restrict__ seg_off, int E, int g_lo, int g_hi,
+                                                  int accumulate) {
+    wgrad_body<WAVES_M, WAVES_N, WM, WN>(p0, p1, p2, seg_off, E, g_lo, g_hi, accumulate);
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
-int run_dgrad(const fine_shape& s, const uint16_t* dy, const uint16_t* act, const uint16_t* wg, const uint16_t* wu,
+int run_dgrad(const fine_shape& s, int rank_lo, int rank_hi, const uint16_t* dy, const uint16_t* act, const uint16_t* wg, const uint16_t* wu,
               const uint16_t* wd, const int32_t* seg_off, uint16_t* dact, uint16_t* h, uint16_t* dxp,
               TileEntry* tiles, int32_t* count, int max_tiles, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
-    FINE_TRY(launch_tile_map(s, seg_off, 0, s.G, BM, tiles, count, max_tiles, st));
+    FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
     const size_t lds = (size_t)2 * (BM + BN) * 128;
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
     constexpr int threads = WAVES_M * WAVES_N * 64;
     auto k1 = [] { if constexpr (W8) return k_bwd_dh_w8<WAVES_M, WAVES_N, WM, WN>; else return k_bwd_dh<WAVES_M, WAVES_N, WM, WN>; }();
     auto k2 = [] { if constexpr (W8) return k_bwd_dx_w8<WAVES_M, WAVES_N, WM, WN>; else return k_bwd_dx<WAVES_M, WAVES_N, WM, WN>; }();
-    static bool attr_done = false;
-    if (!attr_done) {
-        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k1, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
-        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_set1{0}, lds_set2{0};
+    FINE_TRY(raise_lds_limit((const void*)k1, (int)lds, lds_set1));
+    FINE_TRY(raise_lds_limit((const void*)k2, (int)lds, lds_set2));
     const int grid = 256 * ((lds <= 80 * 1024) ? 2 : 1);
     hipLaunchKernelGGL(k1, dim3(grid), dim3(threads), lds, st, dy, wd, act, s.d, s.f, dact, h, tiles, count);
     FINE_LAUNCH_CHECK();
@@ -304,30 +305,27 @@ int run_dgrad(const fine_shape& s, const uint16_t* dy, const uint16_t* act, cons
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
-int run_wgrad(const fine_shape& s, const uint16_t* x_perm, const uint16_t* dy, const uint16_t* dact, const uint16_t* h,
+int run_wgrad(const fine_shape& s, int rank_lo, int rank_hi, const uint16_t* x_perm, const uint16_t* dy, const uint16_t* dact, const uint16_t* h,
               const int32_t* seg_off, float* d_wg, float* d_wu, float* d_wd, int accumulate, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     const size_t lds = (size_t)2 * (BM + BN) * 128;
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
     constexpr int threads = WAVES_M * WAVES_N * 64;
     auto k = [] { if constexpr (W8) return k_wgrad_w8<WAVES_M, WAVES_N, WM, WN>; else return k_wgrad<WAVES_M, WAVES_N, WM, WN>; }();
-    static bool attr_done = false;
-    if (!attr_done) {
-        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_set{0};
+    FINE_TRY(raise_lds_limit((const void*)k, (int)lds, lds_set));
     WgradProblem pg{x_perm, s.d, s.d, dact, 2 * s.f, s.f, d_wg};
     WgradProblem pu{x_perm, s.d, s.d, dact + s.f, 2 * s.f, s.f, d_wu};
     WgradProblem pd{h, s.f, s.f, dy, s.d, s.d, d_wd};
     const int grid = 256 * ((lds <= 80 * 1024) ? 2 : 1);
-    hipLaunchKernelGGL(k, dim3(grid), dim3(threads), lds, st, pg, pu, pd, seg_off, s.E, s.G, accumulate);
+    hipLaunchKernelGGL(k, dim3(grid), dim3(threads), lds, st, pg, pu, pd, seg_off, s.E, rank_lo, rank_hi, accumulate);
     FINE_LAUNCH_CHECK();
     return FINE_OK;
 }
 
 }  // namespace
 
-int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, const void* y_perm,
+int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d_out, const void* x_perm, const void* y_perm,
                     const void* act_save, const void* wg, const void* wu, const void* wd,
                     const int32_t* row_of_pair, const int32_t* pair_of_row, const int32_t* seg_off,
                     const float* topk_w, void* d_x, float* d_topk_w, float* d_wg, float* d_wu,
@@ -342,10 +340,14 @@ int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, 
     auto* count = reinterpret_cast<int32_t*>(ws + L.count);
     const uint16_t* act = reinterpret_cast<const uint16_t*>(act_save);
 
-    FINE_TRY(launch_combine_bwd(s, d_out, y_perm, pair_of_row, topk_w, dy, d_topk_w, st));
+    // A call for one rank of several touches only that rank's rows; their intermediate results stay
+    // in the workspace, and the call for the last rank gathers d_x from the rows of all ranks.
+    const bool one_rank = rank_hi - rank_lo < s.G;
+    const int32_t* rank_rows = one_rank ? seg_off + (size_t)rank_lo * (s.E + 1) : nullptr;
+    FINE_TRY(launch_combine_bwd(s, d_out, y_perm, pair_of_row, topk_w, dy, d_topk_w, rank_rows, st));
     if (act == nullptr) {      // recompute the pre-activations A | B
         auto* act_ws = reinterpret_cast<uint16_t*>(ws + L.act);
-        FINE_TRY(launch_ffn_parts(s, 0, s.G, x_perm, wg, wu, wd, seg_off, h, nullptr, act_ws, tiles, count, L.max_tiles,
+        FINE_TRY(launch_ffn_parts(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h, nullptr, act_ws, tiles, count, L.max_tiles,
                                   reinterpret_cast<float*>(ws + L.sk), true, false, st));
         act = act_ws;
     }
@@ -354,7 +356,7 @@ int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, 
     int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
     if (tile == 0) tile = seg_rows >= 384.0 ? 3 : (seg_rows >= 96.0 ? 2 : 1);
 #define FINE_DGRAD(WAM, WAN, WMM, WNN)                                                                        \
-    FINE_TRY((run_dgrad<WAM, WAN, WMM, WNN>(s, dy, act, (const uint16_t*)wg, (const uint16_t*)wu, (const uint16_t*)wd, \
+    FINE_TRY((run_dgrad<WAM, WAN, WMM, WNN>(s, rank_lo, rank_hi, dy, act, (const uint16_t*)wg, (const uint16_t*)wu, (const uint16_t*)wd, \
                                             seg_off, dact, h, dxp, tiles, count, L.max_tiles, st)))
     if (tile == 3) FINE_DGRAD(2, 4, 4, 2);
     else if (tile == 2) FINE_DGRAD(2, 2, 2, 4);
@@ -362,10 +364,10 @@ int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, 
 #undef FINE_DGRAD
     // weight-gradient tiles span the weight matrices, not the segments
     if (s.d >= 256 && s.f >= 256 && tile != 1)
-        FINE_TRY((run_wgrad<2, 4, 4, 2>(s, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+        FINE_TRY((run_wgrad<2, 4, 4, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
     else
-        FINE_TRY((run_wgrad<2, 2, 2, 2>(s, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
-    FINE_TRY(launch_permute_bwd(s, dxp, row_of_pair, d_x, st));
+        FINE_TRY((run_wgrad<2, 2, 2, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+    if (rank_hi == s.G) FINE_TRY(launch_permute_bwd(s, dxp, row_of_pair, d_x, st));
     return FINE_OK;
 }
 

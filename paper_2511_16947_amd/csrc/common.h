@@ -6,6 +6,8 @@
 #include <stdint.h>
 #include <stddef.h>
 
+#include <atomic>
+
 #include "../../include/finemoe.h"
 
 namespace fine {
@@ -29,6 +31,19 @@ inline int check_hip(hipError_t e) {
     } while (0)
 
 #define FINE_LAUNCH_CHECK() FINE_TRY(fine::check_hip(hipGetLastError()))
+
+// Kernels that need more than 64 KB of dynamic LDS have that limit raised before their first launch
+// on a device.  `done` (one static per kernel) holds a bit per device; concurrent first calls may
+// both set the attribute, which is harmless, and no call ever launches before it is set.
+inline int raise_lds_limit(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    FINE_TRY(check_hip(hipGetDevice(&dev)));
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return FINE_OK;
+    FINE_TRY(check_hip(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes)));
+    done.fetch_or(bit, std::memory_order_release);
+    return FINE_OK;
+}
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
@@ -131,7 +146,7 @@ int launch_combine(const fine_shape& s, const void* y_perm, const int32_t* row_o
                    const float* topk_w, void* out, hipStream_t st);
 int launch_combine_bwd(const fine_shape& s, const void* d_out, const void* y_perm,
                        const int32_t* pair_of_row, const float* topk_w,
-                       void* dy_perm, float* d_topk_w, hipStream_t st);
+                       void* dy_perm, float* d_topk_w, const int32_t* rank_rows, hipStream_t st);
 int launch_permute_bwd(const fine_shape& s, const void* dx_perm, const int32_t* row_of_pair,
                        void* d_x, hipStream_t st);
 
@@ -150,7 +165,7 @@ int launch_ffn_parts(const fine_shape& s, int rank_lo, int rank_hi, const void* 
                      void* act_save, TileEntry* tiles, int32_t* count, int max_tiles, float* sk_partials, bool gemm1, bool gemm2,
                      hipStream_t st);
 
-int launch_backward(const fine_shape& s, const void* d_out, const void* x_perm, const void* y_perm,
+int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d_out, const void* x_perm, const void* y_perm,
                     const void* act_save, const void* wg, const void* wu, const void* wd,
                     const int32_t* row_of_pair, const int32_t* pair_of_row, const int32_t* seg_off,
                     const float* topk_w, void* d_x, float* d_topk_w, float* d_wg, float* d_wu,

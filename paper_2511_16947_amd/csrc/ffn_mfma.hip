@@ -118,11 +118,6 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
         }
     };
 
-#ifdef FINE_PROFILE_LOOP
-#define FINE_PROF_TILE(slot) do { if (blockIdx.x == 0 && threadIdx.x == 0 && work / (int)gridDim.x < 8) g_prof[512 + (work / gridDim.x) * 8 + (slot)] = (slot) >= 5 ? wall_clock64() : clock64(); } while (0)
-#else
-#define FINE_PROF_TILE(slot) do { } while (0)
-#endif
     // Whole tiles first: as many full rounds of the grid as there are (4 waves: all tiles).
     // 8 waves: the remaining rest < nblk tiles are rest * nk k-steps; block b takes steps
     // [b * per, (b+1) * per) of that sequence.  A block that computes only part of a tile's k
@@ -164,10 +159,6 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     constexpr int kCoherent = 1 | 16;      // sc0 | sc1
     const __amdgpu_buffer_rsrc_t sk_rs =
         __builtin_amdgcn_make_buffer_rsrc((void*)sk_partials, 0, (int)(2 * 256 * (size_t)kSlotBytes), 0x00020000);
-#ifdef FINE_PROFILE_LOOP
-    const unsigned long long blk_w0 = wall_clock64(), blk_c0 = clock64();
-    int blk_tiles = 0;
-#endif
     int next_whole = bid, u = bid * per;
     const int u1 = min(rest * nk, u + per);
     bool part_taken = false;
@@ -191,11 +182,8 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
         } else {
             break;
         }
-        FINE_PROF_TILE(0);
-        FINE_PROF_TILE(5);
         zero_acc<WM, WN>(acc);
         run_tile(work, kb, kn);
-        FINE_PROF_TILE(1);
         bool finish = true;
         if constexpr (W8) {
             if (kn != nk) {
@@ -246,20 +234,7 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
             }
         }
         if (finish) epilogue(work);
-        FINE_PROF_TILE(2);
-        FINE_PROF_TILE(6);
-#ifdef FINE_PROFILE_LOOP
-        ++blk_tiles;
-#endif
     }
-#ifdef FINE_PROFILE_LOOP
-    if (threadIdx.x == 0 && blockIdx.x < 256) {
-        g_prof[1024 + blockIdx.x * 4 + 0] = blk_w0;
-        g_prof[1024 + blockIdx.x * 4 + 1] = wall_clock64();
-        g_prof[1024 + blockIdx.x * 4 + 2] = clock64() - blk_c0;
-        g_prof[1024 + blockIdx.x * 4 + 3] = blk_tiles;
-    }
-#endif
 }
 
 template <int WAVES_M, int WAVES_N, int WM, int WN, int EPI>
@@ -302,12 +277,9 @@ int run_ffn(const fine_shape& s, int rank_lo, int rank_hi, const void* x_perm, c
     auto k1 = ffn_kernel<WAVES_M, WAVES_N, WM, WN, 0>();
     auto k2 = ffn_kernel<WAVES_M, WAVES_N, WM, WN, 1>();
     constexpr int threads = WAVES_M * WAVES_N * 64;
-    static bool attr_done = false;      // per instantiation
-    if (!attr_done) {
-        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k1, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
-        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k2, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)));
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_set1{0}, lds_set2{0};      // per instantiation
+    FINE_TRY(raise_lds_limit((const void*)k1, (int)lds, lds_set1));
+    FINE_TRY(raise_lds_limit((const void*)k2, (int)lds, lds_set2));
     const int blocks_per_cu = (lds <= 80 * 1024) ? 2 : 1;
     const int grid = 256 * blocks_per_cu;
     if (gemm1) {
@@ -377,8 +349,3 @@ int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x
 
 }  // namespace fine
 
-#ifdef FINE_PROFILE_LOOP
-extern "C" __attribute__((visibility("default"))) int fine_debug_prof(unsigned long long* host_out) {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(fine::mfma::g_prof), sizeof(unsigned long long) * (128 * 8 + 1024));
-}
-#endif

@@ -131,11 +131,6 @@ struct LoaderMC {
         const int kblock = u & 7, r0 = (u >> 3) * 8;
         constexpr uint32_t sel = (M & 1) ? 0x07060302u : 0x05040100u;
         u32x4 o;
-#ifdef FINE_DBG_NOPERM
-        o = reg[SET][M];
-        *reinterpret_cast<u32x4*>(lds + lds_off(r0 + M, kblock)) = o;
-        return;
-#endif
         o.x = __builtin_amdgcn_perm(reg[SET][1][M >> 1], reg[SET][0][M >> 1], sel);
         o.y = __builtin_amdgcn_perm(reg[SET][3][M >> 1], reg[SET][2][M >> 1], sel);
         o.z = __builtin_amdgcn_perm(reg[SET][5][M >> 1], reg[SET][4][M >> 1], sel);
@@ -340,16 +335,6 @@ __device__ inline int xcd_contiguous_id() {
 
 constexpr int share_begin(int slot, int total, int slots) { return (total * slot) / slots; }
 
-#ifdef FINE_PROFILE_LOOP
-// scratch instrumentation (never in the shipped build): cycle stamps of block 0, wave 0
-static __device__ unsigned long long g_prof[128 * 8 + 1024];    // + per block: start, end (wall clock), clock64 span, tiles
-#define FINE_PROF(slot)                                                                          \
-    do {                                                                                         \
-        if (blockIdx.x == 0 && threadIdx.x == 0 && kt < 64) g_prof[kt * 8 + (slot)] = clock64(); \
-    } while (0)
-#else
-#define FINE_PROF(slot) do { } while (0)
-#endif
 
 // ---------------------------------------------------------------------------
 // One k-step (64 k-values) with a hand-fixed instruction order.
@@ -389,9 +374,6 @@ __device__ inline void k_step(const char* sA, const char* sB, char* nA, char* nB
     bf16x8 af[2][WM], bfr[2][WN];
 
     auto read_frag = [&](auto kk, auto idx, auto set) {      // idx < WM: A fragment, else B fragment
-#ifdef FINE_DBG_NOLDSREAD
-        if (kk.value > 0) return;
-#endif
         if constexpr (idx.value < WM)
             af[set.value][idx.value] = *reinterpret_cast<const bf16x8*>(
                 sA + lds_off((wm * WM + idx.value) * 32 + r, 2 * kk.value + half));
@@ -403,9 +385,6 @@ __device__ inline void k_step(const char* sA, const char* sB, char* nA, char* nB
     // reloads of A (piece by piece where a piece may be reloaded at once), the loads of B.
     auto side_op = [&](auto op) {
         constexpr int o = op.value;
-#ifdef FINE_DBG_NOSTORE
-        if constexpr (o < NB || (o < NB + 2 * NA && (LA::kPieceRecycle ? ((o - NB) % 2 == 0) : (o - NB < NA)))) return;
-#endif
         if constexpr (o < NB) {
             if constexpr (STORE) lb.template store_one<o, ST_B>(nB);
         } else if constexpr (o < NB + 2 * NA) {
@@ -415,14 +394,10 @@ __device__ inline void k_step(const char* sA, const char* sB, char* nA, char* nB
             if constexpr (is_store) {
                 if constexpr (STORE) la.template store_one<p, ST_A>(nA);
             } else {
-#ifndef FINE_DBG_NOLOADA
                 if constexpr (LOAD) la.template load_one<p, LD_A>(next.a, next.end);
-#endif
             }
         } else {
-#ifndef FINE_DBG_NOLOADB
             if constexpr (LOAD) lb.template load_one<o - NB - 2 * NA, LD_B>(next.b, next.end);
-#endif
         }
     };
     constexpr int NOPS = 2 * (NA + NB);
@@ -436,11 +411,7 @@ __device__ inline void k_step(const char* sA, const char* sB, char* nA, char* nB
             static_for<2>([&](auto t) {
                 constexpr int m = 2 * j.value + t.value;
                 constexpr int mi = m / WN, ni = m % WN;
-#ifdef FINE_DBG_NOMFMA
-                if (af[cur][mi][0] == (__bf16)12345.f && bfr[cur][ni][1] == (__bf16)777.f) acc[mi][ni][0] += 1.f;
-#else
                 acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ni], af[cur][mi], acc[mi][ni], 0, 0, 0);
-#endif
             });
             if constexpr (kk.value < 3) {      // fragment reads of the next sub-step
                 constexpr int b = share_begin(j.value, DSR, SL), e = share_begin(j.value + 1, DSR, SL);
@@ -495,11 +466,8 @@ __device__ inline void k_loop(int nk, char* smem, f32x16 (&acc)[WM][WN], LA& la,
     constexpr int P0 = (D == 2) ? 1 : 0;
     int kt = 0;
     for (; kt + 2 < nk; kt += 2) {       // both steps write a tile that will be used
-        FINE_PROF(0);
         k_step<WAVES_M, WAVES_N, WM, WN, D, P0, true, true>(sA(0), sB(0), sA(1), sB(1), acc, la, lb, next_tile());
-        FINE_PROF(3);
         __syncthreads();
-        FINE_PROF(4);
         k_step<WAVES_M, WAVES_N, WM, WN, D, P0 ^ 1, true, true>(sA(1), sB(1), sA(0), sB(0), acc, la, lb, next_tile());
         __syncthreads();
     }

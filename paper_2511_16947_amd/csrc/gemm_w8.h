@@ -286,43 +286,33 @@ struct Frags {
 template <int P, bool BARRIER, bool RAGGED_M, int RING, bool ISSUE, int WM, typename OA, typename OB>
 __device__ inline void half_step8(const char* a_src, const char* b_src, const char* a_next, const char* b_next,
                                   char* a_dst, char* b_dst, f32x16 (&acc)[WM][2], Frags<WM>& f0, Frags<WM>& f1, OA& oa,
-                                  OB& ob, ptrdiff_t ka, ptrdiff_t kb, int kbase, int kend, int ksel, int nf, int prof_kt = 0) {
+                                  OB& ob, ptrdiff_t ka, ptrdiff_t kb, int kbase, int kend, int ksel, int nf) {
     constexpr int WN = 2;
     using S = Schedule<OA::kKind, OB::kKind, WM>;
     constexpr bool ringA = OA::kKind == kRing, ringB = OB::kKind == kRing;
     constexpr int KA1 = ringA ? 1 : 2 * P + 1, KB1 = ringB ? 1 : 2 * P + 1;                 // second sub-step
     constexpr int KA0 = ringA ? 0 : (2 * P + 2) & 3, KB0 = ringB ? 0 : (2 * P + 2) & 3;     // next first
     auto side = [&](auto slot_c) {
-#ifndef FINE_DBG_NOSIDE
         if constexpr (ISSUE) static_for<2>([&](auto which) {
             constexpr SideOp o = S::op[P][slot_c.value][which.value];
-#ifdef FINE_DBG_NODMA
-            if constexpr (is_dma(o)) return;
-#endif
             if constexpr (o.kind == kDmaA) oa.template issue<o.idx>(ka, kbase, kend, a_dst);
             else if constexpr (o.kind == kDmaB) ob.template issue<o.idx>(kb, kbase, kend, b_dst);
             else if constexpr (o.kind == kRowA) oa.template row_issue<o.idx>(ka, 0, a_dst);
             else if constexpr (o.kind == kRowB) ob.template row_issue<o.idx>(kb, ksel, b_dst);
         });
-#endif
     };
     auto mfma_pair = [&](auto j, const Frags<WM>& f) {
         static_for<2>([&](auto t) {
             constexpr int m = 2 * j.value + t.value;
             constexpr int mi = m / WN, ni = m % WN;
             if (RAGGED_M && mi >= nf) return;
-#ifndef FINE_DBG_NOMFMA
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[mi][ni], 0, 0, 0);
-#else
-            acc[mi][ni][0] += (float)f.b[ni][0] + (float)f.a[mi][0];
-#endif
         });
     };
     // Fragment reads are spread over the slots (B fragments in slot 0, A fragments in slots 1
     // and 2): issued in one burst they would keep the MFMA pipe idle for their issue time,
     // since both waves of a SIMD reach that point together.
     auto reads = [&](auto slot_c, Frags<WM>& f, auto ka_c, auto kb_c, const char* a_from, const char* b_from) {
-#ifndef FINE_DBG_NOLDSREAD
         constexpr int KA = ka_c.value, KB = kb_c.value;
         if constexpr (slot_c.value == 0) {
             if (RAGGED_M && nf == 0) return;      // a wave without valid rows reads nothing
@@ -334,7 +324,6 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
                 f.a[fi] = oa.template frag<KA, fi>(a_from);
             });
         }
-#endif
     };
     // first sub-step: MFMAs on f0 while the second sub-step's fragments arrive in f1
     static_for<WM>([&](auto j) {
@@ -343,16 +332,10 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
         side(IntC<j.value>{});
         __builtin_amdgcn_sched_barrier(0);
     });
-#ifdef FINE_PROFILE_LOOP
-    if (blockIdx.x == 0 && threadIdx.x == 0 && prof_kt < 64) g_prof[prof_kt * 8 + 1 + 4 * P] = clock64();
-#endif
     if constexpr (BARRIER) {
         wait_vm_lgkm<(ISSUE ? vm_allowed<S, RING>(P) : 0)>();
         block_barrier();
     }
-#ifdef FINE_PROFILE_LOOP
-    if (blockIdx.x == 0 && threadIdx.x == 0 && prof_kt < 64) g_prof[prof_kt * 8 + 2 + 4 * P] = clock64();
-#endif
     // second sub-step: MFMAs on f1 while the next half step's first fragments arrive in f0
     static_for<WM>([&](auto j) {
         reads(j, f0, IntC<KA0>{}, IntC<KB0>{}, a_next, b_next);
@@ -438,19 +421,16 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[WM][2], OA& oa,
     KTile n2 = n1;
     auto iteration = [&](int kt, auto issue0, auto issue1) {
         const int h = 2 * kt;
-        FINE_PROF(0);
         const KTile& d0 = (RING == 4) ? n1 : n2;      // ring, P = 0
         constexpr int d0_half = (RING == 4) ? 32 : 0, d1_half = (RING == 4) ? 0 : 32;
         half_step8<0, kAnyRing, RAGGED_M, RING, issue0.value, WM>(
             a_at(kt, h), b_at(kt, h), a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + RING - 1),
             b_at(kt + 1, h + RING - 1), acc, f0, f1, oa, ob, kA == kRing ? d0.a + d0_half : n2.a,
-            kB == kRing ? d0.b + d0_half : n2.b, d0.base, d0.end, 0, nf, kt);
-        FINE_PROF(3);
+            kB == kRing ? d0.b + d0_half : n2.b, d0.base, d0.end, 0, nf);
         half_step8<1, true, RAGGED_M, RING, issue1.value, WM>(
             a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + 2), b_at(kt + 1, h + 2),
             kA == kRow ? a_at(kt, 0) : a_at(kt + 1, h + RING), kB == kRow ? b_at(kt, 0) : b_at(kt + 1, h + RING), acc, f0,
-            f1, oa, ob, kA == kRing ? n2.a + d1_half : n2.a, kB == kRing ? n2.b + d1_half : n2.b, n2.base, n2.end, n2.sel, nf, kt);
-        FINE_PROF(7);
+            f1, oa, ob, kA == kRing ? n2.a + d1_half : n2.a, kB == kRing ? n2.b + d1_half : n2.b, n2.base, n2.end, n2.sel, nf);
     };
     int kt = 0;
     for (; kt + 2 < nk; ++kt) {

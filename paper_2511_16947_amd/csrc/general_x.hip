@@ -189,12 +189,8 @@ int launch_general_x(const fine_shape& s, const uint8_t* place, const int32_t* l
                      int32_t* x_eg, int32_t* max_load, hipStream_t st) {
     const size_t lds = flow::ctx_bytes(s.E, s.G);
     if (lds > 160 * 1024) return FINE_UNSUPPORTED;
-    static bool attr_done = false;
-    if (!attr_done) {
-        FINE_TRY(check_hip(hipFuncSetAttribute((const void*)k_general_x, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               160 * 1024)));
-        attr_done = true;
-    }
+    static std::atomic<uint64_t> lds_set{0};
+    FINE_TRY(raise_lds_limit((const void*)k_general_x, 160 * 1024, lds_set));
     hipLaunchKernelGGL(k_general_x, dim3(1), dim3(64), lds, st, place, load, x_prev, s.E, s.G, s.T * s.K, x_eg, max_load);
     FINE_LAUNCH_CHECK();
     return FINE_OK;

@@ -141,9 +141,12 @@ template <typename T, int VEC>
 __global__ __launch_bounds__(256) void k_combine_bwd(const T* __restrict__ d_out, const T* __restrict__ y_perm,
                                                      const int32_t* __restrict__ pair_of_row,
                                                      const float* __restrict__ topk_w, T* __restrict__ dy_perm,
-                                                     float* __restrict__ d_topk_w, int P, int K, int d) {
+                                                     float* __restrict__ d_topk_w, int P, int K, int d,
+                                                     const int32_t* __restrict__ rank_rows, int E) {
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= P) return;
+    // one rank's rows only: rank_rows points at its row of seg_off (first row .. end of the rank)
+    if (rank_rows != nullptr && (row < rank_rows[0] || row >= rank_rows[E])) return;
     const int lane = threadIdx.x & 63;
     const int p = pair_of_row[row];
     const int t = p / K;
@@ -298,15 +301,15 @@ int launch_combine(const fine_shape& s, const void* y_perm, const int32_t* row_o
 
 int launch_combine_bwd(const fine_shape& s, const void* d_out, const void* y_perm,
                        const int32_t* pair_of_row, const float* topk_w,
-                       void* dy_perm, float* d_topk_w, hipStream_t st) {
+                       void* dy_perm, float* d_topk_w, const int32_t* rank_rows, hipStream_t st) {
     const int P = s.T * s.K;
     if (P == 0) return FINE_OK;
     if (s.dtype == FINE_F32) {
         auto* g = (const float*)d_out; auto* y = (const float*)y_perm; auto* o = (float*)dy_perm;
-        FINE_DISPATCH_ROWS(k_combine_bwd, float, P, g, y, pair_of_row, topk_w, o, d_topk_w, P, s.K, s.d);
+        FINE_DISPATCH_ROWS(k_combine_bwd, float, P, g, y, pair_of_row, topk_w, o, d_topk_w, P, s.K, s.d, rank_rows, s.E);
     } else {
         auto* g = (const uint16_t*)d_out; auto* y = (const uint16_t*)y_perm; auto* o = (uint16_t*)dy_perm;
-        FINE_DISPATCH_ROWS(k_combine_bwd, uint16_t, P, g, y, pair_of_row, topk_w, o, d_topk_w, P, s.K, s.d);
+        FINE_DISPATCH_ROWS(k_combine_bwd, uint16_t, P, g, y, pair_of_row, topk_w, o, d_topk_w, P, s.K, s.d, rank_rows, s.E);
     }
     FINE_LAUNCH_CHECK();
     return FINE_OK;

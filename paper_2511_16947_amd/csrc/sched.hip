@@ -192,7 +192,10 @@ __global__ __launch_bounds__(256) void k_pairs(const int32_t* __restrict__ topk_
     if (p >= T * K) return;
     const int t = p / K;
     const int e = topk_idx[p];
-    if (e < 0 || e >= E) { pair_dst[p] = -1; row_of_pair[p] = -1; return; }
+    // A pair without a destination (an expert index out of range; no schedule exists because an
+    // expert with load has no replica) keeps its own place: row p <-> pair p.  pair_dst = -1 marks
+    // it, and the movement kernels that run on these indices afterwards stay inside their buffers.
+    if (e < 0 || e >= E) { pair_dst[p] = -1; row_of_pair[p] = p; pair_of_row[p] = p; return; }
     const int g = t / (T / G);
     const int w = t >> 6;
     int r = cum[(size_t)e * (W + 1) + w] + __popcll(bitmap[(size_t)e * W + w] & ((1ull << (t & 63)) - 1ull))
@@ -211,7 +214,7 @@ __global__ __launch_bounds__(256) void k_pairs(const int32_t* __restrict__ topk_
             r -= c;
         }
     }
-    if (dst < 0) { pair_dst[p] = -1; row_of_pair[p] = -1; return; }   // unreachable for a consistent table
+    if (dst < 0) { pair_dst[p] = -1; row_of_pair[p] = p; pair_of_row[p] = p; return; }   // no schedule exists
     const int row = seg_off[(size_t)dst * (E + 1) + e] + Ypre[((size_t)e * G + g) * G + dst] + within;
     pair_dst[p] = dst;
     row_of_pair[p] = row;

@@ -24,9 +24,9 @@ class GpuBackward:
         self.d_wu = torch.full((s.E, s.d, s.f), float("nan"), dtype=torch.float32, device=dev)
         self.d_wd = torch.full((s.E, s.f, s.d), float("nan"), dtype=torch.float32, device=dev)
 
-    def run(self, accumulate=False):
+    def run(self, accumulate=False, rank=-1):
         L, i = self.layer, self.layer.inp
-        fm.fine_backward(L.shape, -1, i.d_out, L.x_perm, L.y_perm, L.act_save, i.w_gate, i.w_up, i.w_down,
+        fm.fine_backward(L.shape, rank, i.d_out, L.x_perm, L.y_perm, L.act_save, i.w_gate, i.w_up, i.w_down,
                          L.sb.row_of_pair, L.sb.pair_of_row, L.sb.seg_off, L.topk_w, self.d_x, self.d_topk_w,
                          self.d_wg, self.d_wu, self.d_wd, accumulate, self.ws)
         torch.cuda.synchronize()
@@ -104,6 +104,43 @@ def test_backward_under_a_restricted_placement(tile):
                 assert max_rel_err(to64(got[e]), g[key][e]) <= TOL, (key, e)
             else:
                 assert not got[e].any(), (key, e)
+
+
+@pytest.mark.parametrize("tile", [0, 3])
+@pytest.mark.parametrize("saved", [False, True])
+def test_backward_rank_by_rank(tile, saved):
+    """One fine_backward call per rank in ascending order (rank 0 overwriting the weight gradients,
+    the others adding to them) against one call for all ranks: d_x and d_topk_w bit-equal, the weight
+    gradients equal up to fp32 summation order and within tolerance of the oracle.  Under a
+    restricted placement, so that experts really are split over ranks."""
+    cfg = wl.scaled(wl.CONFIGS["cfg5_train"], name="cfg5_ranks", T=1024, d=128, f=256, E=16, K=2, G=8,
+                    bias_kind="scaled_z", bias_scale=1.5)
+    inp = wl.make_inputs(cfg, DEV)
+    place = torch.from_numpy(wl.placement_z2xz4()).to(DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+    if saved:
+        layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+    layer.forward(place=place)
+    whole = GpuBackward(layer)
+    whole.run()
+    parts = GpuBackward(layer)
+    for r in range(cfg.G):
+        parts.run(accumulate=(r > 0), rank=r)
+    assert torch.equal(parts.d_x.view(torch.int16), whole.d_x.view(torch.int16))
+    assert torch.equal(parts.d_topk_w, whole.d_topk_w)
+    idx = layer.topk_idx.cpu().numpy()
+    g = moe.backward_dense(to64(inp.x), idx, to64(layer.topk_w), weights_of_factory(inp), to64(inp.d_out))
+    for got, ref, key in ((parts.d_wg, whole.d_wg, "d_w_gate"), (parts.d_wu, whole.d_wu, "d_w_up"),
+                          (parts.d_wd, whole.d_wd, "d_w_down")):
+        assert max_rel_err(to64(got), to64(ref)) <= 1e-5, key
+        for e in range(cfg.E):
+            if e in g[key]:
+                assert max_rel_err(to64(got[e]), g[key][e]) <= TOL, (key, e)
+            else:
+                assert not got[e].any(), (key, e)
+    # a rank out of range is an argument error
+    with pytest.raises(fm.FineError):
+        parts.run(rank=cfg.G)
 
 
 def test_backward_full_size_cfg5():

@@ -109,3 +109,16 @@ def test_expert_without_replica_is_reported():
     torch.cuda.synchronize()
     assert int(sb.max_load.cpu()[0]) == -1
     assert not sb.x_eg.any()
+    # nothing is scheduled, and what the movement and FFN entry points would read stays in bounds
+    assert bool((sb.pair_dst == -1).all().cpu())
+    ident = torch.arange(T * K, dtype=torch.int32, device=DEV)
+    assert torch.equal(sb.row_of_pair, ident) and torch.equal(sb.pair_of_row, ident)
+    assert not sb.seg_off.any() and not sb.rank_off.any()
+    layer_shape = fm.Shape(T, 64, 64, E, K, G, fm.FINE_BF16, fm.FLAG_LOCALITY)
+    x = torch.randn(T, 64, device=DEV).bfloat16()
+    x_perm = torch.zeros(T * K, 64, dtype=torch.bfloat16, device=DEV)
+    out = torch.zeros(T, 64, dtype=torch.bfloat16, device=DEV)
+    fm.fine_permute(layer_shape, x, sb.pair_of_row, x_perm)
+    fm.fine_combine(layer_shape, x_perm, sb.row_of_pair, torch.ones(T, K, device=DEV), out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, x)

@@ -107,7 +107,10 @@ def test_warm_start_still_reports_an_expert_without_replica():
     torch.cuda.synchronize()
     assert int(sb.max_load.cpu()[0]) == -1
     assert int(sb.x_eg.abs().sum().cpu()) == 0
-    assert bool((sb.pair_dst == -1).all().cpu()) and bool((sb.row_of_pair == -1).all().cpu())
+    assert bool((sb.pair_dst == -1).all().cpu())
+    ident = torch.arange(T * K, dtype=torch.int32, device=sb.row_of_pair.device)
+    assert torch.equal(sb.row_of_pair, ident) and torch.equal(sb.pair_of_row, ident)
+    assert not sb.seg_off.any() and not sb.rank_off.any()
 
 
 def test_scheduling_on_a_second_stream_gives_the_in_line_results():
