@@ -145,6 +145,24 @@ int fine_sched_warm(const fine_shape* shape, const int32_t* topk_idx, const uint
                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * fine_sched for callers that cannot allocate or pass device scratch memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without ws) and
+ * the same results, bit for bit, as fine_sched; the tables fine_sched keeps in `ws` live in a
+ * 4 MiB array inside the library's device image instead (each GPU the library runs on holds its
+ * own copy until the process ends).  The call allocates and frees nothing.
+ *   Limit: fine_workspace_bytes(shape, FINE_WS_SCHED) <= 4 MiB (all five workloads this library is
+ *   measured on fit: the largest, 256 experts on 32 ranks, needs 2.3 MiB), else
+ *   FINE_WORKSPACE_TOO_SMALL; shapes fine_sched rejects are rejected alike.
+ *   Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two streams,
+ *   two threads) race and must be ordered by the caller.  Nothing in the array has to survive
+ *   between calls or start at zero.
+ */
+int fine_sched_static(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
+                      int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
+                      int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+                      int32_t* seg_off, int32_t* rank_off, void* stream);
+
+/*
  * Permutation (Section 4.4: replicate tokens by top-K and sort them before dispatch).
  * x_perm[row] = x[pair_of_row[row] / K].   x [T,d] dtype -> x_perm [P,d] dtype.
  */

@@ -30,7 +30,7 @@ FLAG_LOCALITY, FLAG_SIMPLE_FFN, FLAG_ONLY_GEMM1, FLAG_ONLY_GEMM2 = 1, 2, 4, 8
 WS_TOPK, WS_SCHED, WS_FFN, WS_BACKWARD = 0, 1, 2, 3
 
 EXPORTS = ["fine_version", "fine_last_hip_error", "fine_workspace_bytes", "fine_topk", "fine_sched",
-           "fine_sched_warm",
+           "fine_sched_warm", "fine_sched_static",
            "fine_permute", "fine_grouped_ffn", "fine_combine", "fine_backward", "fine_replica_counts",
            "fine_eval_placements", "fine_place_search"]
 
@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.fine_sched.argtypes = [sp] + [vp] * 11 + [vp, sz, vp]
     lib.fine_sched_warm.restype = ctypes.c_int
     lib.fine_sched_warm.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
+    lib.fine_sched_static.restype = ctypes.c_int
+    lib.fine_sched_static.argtypes = [sp] + [vp] * 11 + [vp]
     lib.fine_permute.restype = ctypes.c_int
     lib.fine_permute.argtypes = [sp, vp, vp, vp, vp]
     lib.fine_grouped_ffn.restype = ctypes.c_int
@@ -169,6 +171,15 @@ def fine_sched_warm(shape: Shape, topk_idx, place, x_prev, load, input_eg, x_eg,
                                         _ptr(input_eg), _ptr(x_eg), _ptr(max_load), _ptr(pair_dst), _ptr(row_of_pair),
                                         _ptr(pair_of_row), _ptr(seg_off), _ptr(rank_off), _ptr(ws), ws.numel(), _stream())
     _check("fine_sched_warm", rc)
+
+
+def fine_sched_static(shape: Shape, topk_idx, place, load, input_eg, x_eg, max_load, pair_dst, row_of_pair, pair_of_row,
+                      seg_off, rank_off):
+    cs = shape.c()
+    rc = load_library().fine_sched_static(ctypes.byref(cs), _ptr(topk_idx), _ptr(place), _ptr(load), _ptr(input_eg),
+                                          _ptr(x_eg), _ptr(max_load), _ptr(pair_dst), _ptr(row_of_pair),
+                                          _ptr(pair_of_row), _ptr(seg_off), _ptr(rank_off), _stream())
+    _check("fine_sched_static", rc)
 
 
 def fine_permute(shape: Shape, x, pair_of_row, x_perm):

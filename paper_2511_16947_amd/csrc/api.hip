@@ -101,6 +101,23 @@ int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* 
                            pair_of_row, seg_off, rank_off, ws, ws_bytes, stream);
 }
 
+int fine_sched_static(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
+                      int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
+                      int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+                      int32_t* seg_off, int32_t* rank_off, void* stream) {
+    FINE_TRY(check_shape(shape));
+    if (!topk_idx || !load || !input_eg || !x_eg || !max_load || !pair_dst || !row_of_pair || !pair_of_row ||
+        !seg_off || !rank_off)
+        return FINE_INVALID_ARG;
+    if (shape->T == 0) return FINE_INVALID_ARG;
+    if (sched_ws_layout(*shape).total > kSchedStaticBytes) return FINE_WORKSPACE_TOO_SMALL;
+    char* ws = nullptr;
+    FINE_TRY(sched_static_scratch(&ws));
+    // every table in the scratch array is written in full before it is read: nothing to clear
+    return launch_sched(*shape, topk_idx, place, nullptr, load, input_eg, x_eg, max_load, pair_dst, row_of_pair,
+                        pair_of_row, seg_off, rank_off, ws, (hipStream_t)stream);
+}
+
 int fine_permute(const fine_shape* shape, const void* x, const int32_t* pair_of_row, void* x_perm, void* stream) {
     FINE_TRY(check_shape(shape));
     if (!x || !pair_of_row || !x_perm) return FINE_INVALID_ARG;

@@ -141,6 +141,11 @@ int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* pl
                  int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
                  int32_t* seg_off, int32_t* rank_off, char* ws, hipStream_t st);
 
+// fine_sched_static: size of the scratch array in the device image, and its address on the current
+// device (asked for on the first call there; no allocation).
+constexpr size_t kSchedStaticBytes = (size_t)4 << 20;
+int sched_static_scratch(char** ptr);
+
 int launch_permute(const fine_shape& s, const void* x, const int32_t* pair_of_row, void* x_perm, hipStream_t st);
 int launch_combine(const fine_shape& s, const void* y_perm, const int32_t* row_of_pair,
                    const float* topk_w, void* out, hipStream_t st);

@@ -277,4 +277,33 @@ int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* pl
     return FINE_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Scratch memory of fine_sched_static: an array in the library's device image, for callers that
+// cannot hand over (or allocate) a workspace.  Each GPU holds its own copy of the array at its own
+// address, and the array's name is only a host-side handle, never a device address: the address is
+// asked for once per device, with that device current, and that pointer is what the kernels get.
+// ---------------------------------------------------------------------------
+namespace {
+
+static __device__ __align__(256) unsigned char scratch[kSchedStaticBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];      // zero-initialised: not asked for yet
+
+}  // namespace
+
+int sched_static_scratch(char** out) {
+    int dev = 0;
+    FINE_TRY(check_hip(hipGetDevice(&dev)));
+    if (dev < 0 || dev >= kMaxDevices) return FINE_UNSUPPORTED;
+    unsigned char* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        FINE_TRY(check_hip(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch))));
+        if (ptr == nullptr) return FINE_HIP_ERROR;
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);      // concurrent first calls store the same address
+    }
+    *out = reinterpret_cast<char*>(ptr);
+    return FINE_OK;
+}
+
 }  // namespace fine
