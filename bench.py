@@ -1,12 +1,15 @@
 #!/usr/bin/env python3
 """One-GPU benchmark of the scheduled MoE-layer hot path.
 
-A step = one pass of the whole forward hot path over one synthetic batch that is
-already resident in HBM: gate top-K, token scheduling, permute, grouped SwiGLU expert
-FFN for every logical rank (one rank after another), combine; for the training
-workload (cfg5_train) the backward pass as well.  Prints ONE JSON line.
+A step = one pass of the whole hot path over one synthetic batch that is already resident
+in HBM: gate top-K, token scheduling, permute, grouped SwiGLU expert FFN for every logical
+rank (one rank after another), combine; for the training workload (cfg5_train, the default:
+the largest of the five workloads) the backward pass as well.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2_mixtral]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg5_train]
+
+The default run also times the four other workloads briefly (detail.other_workloads: layer
+TFLOP/s, per-rank time and row balance, experts per rank; for cfg2_mixtral the GEMM 1 roofline).
 
     python bench.py --placement-search [--config cfg5_train]
 times the other device path instead, the placement construction from known expert loads
@@ -26,10 +29,12 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
 
 
-# Counter readings of the GEMM 1 kernel (mean KiB per launch over a default run of this file under
-# rocprofv3 --pmc; profiles/ffn_gemm1_w8_cfg2_mixtral_hbm_counters.md), scaled by what the same
-# counters read for --copy-calibration: FETCH_SIZE 0.5 per byte read, WRITE_SIZE 1.0 per byte written.
+# Counter readings (mean KiB per launch under rocprofv3 --pmc; the summaries under profiles/ give the
+# commands), scaled by what the same counters read for --copy-calibration: FETCH_SIZE 0.5 per byte read,
+# WRITE_SIZE 1.0 per byte written.  GEMM 1 of a rank on cfg2_mixtral; the weight-gradient kernel of cfg5_train.
 GEMM1_TRAFFIC_BYTES = {"cfg2_mixtral": int(687043.3 * 1024 * 2.0 + 96261.2 * 1024 * 1.0)}
+WGRAD_TRAFFIC_BYTES = {}
+BASELINE_METRIC = "MoE layer TFLOP/s per GPU (sched+permute+grouped GEMM+combine); max/mean rank load"
 
 
 def parse():
@@ -37,7 +42,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="cfg2_mixtral")
+    ap.add_argument("--config", default="cfg5_train")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the brief runs of the other four workloads that the default run appends")
     ap.add_argument("--ffn", choices=["per_rank", "fused"], default="per_rank",
                     help="per_rank: one fine_grouped_ffn call per logical rank (default); fused: one call for all")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -100,6 +107,29 @@ def main():
     if args.stream:
         run_stream(args, cfg, dev)
         return
+    line = run_layer(args, cfg, dev, args.steps, args.warmup, cpu=not args.no_cpu_baseline, restricted=True)
+    if args.config == "cfg5_train" and not args.no_other_workloads and args.placement == "full" and args.ffn == "per_rank":
+        # the other four workloads, briefly: what the targets are read on besides the headline
+        other = {}
+        for name in ("cfg1_tiny_f32", "cfg2_mixtral", "cfg3_finegrained", "cfg4_dsv3"):
+            torch.cuda.empty_cache()
+            l2 = run_layer(args, wl.CONFIGS[name], dev, 20, 5, cpu=False, restricted=False)
+            d2 = l2["detail"]
+            other[name] = {"TFLOPs": l2["value"], "ms_per_step": l2["ms_per_step"], "steps": 20, "warmup": 5,
+                           "rank_load": l2["rank_load"], "stage_ms": d2["stage_ms"],
+                           "ffn_TFLOPs_per_rank_calls": d2["ffn_TFLOPs_per_rank_calls"], "roofline": l2["roofline"]}
+        line["detail"]["other_workloads"] = other
+    print(json.dumps(line))
+
+
+def run_layer(args, cfg, dev, steps, warmup, cpu, restricted):
+    """Times the whole hot path on one workload and returns the JSON line as a dict."""
+    import numpy as np
+    import torch
+
+    import paper_2511_16947_amd as fm
+    import workloads as wl
+
     t_gen = time.time()
     inp = wl.make_inputs(cfg, dev)
     torch.cuda.synchronize()
@@ -170,9 +200,24 @@ def main():
     def st_combine():
         fm.fine_combine(s, y_perm, sb.row_of_pair, topk_w, out)
 
-    def st_backward():
-        fm.fine_backward(s, -1, inp.d_out, x_perm, y_perm, act_save, inp.w_gate, inp.w_up, inp.w_down, sb.row_of_pair,
+    # The backward entry point is issued stage by stage (the same kernels in the same order as one
+    # call; a measurement switch of the library), so that HIP events on the launch stream can bracket
+    # the step's dominant kernel, the weight gradients, inside the timed steps themselves.
+    wgrad_events = []
+    bwd_shapes = [fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | (k << fm.FLAG_BWD_STAGE_SHIFT))
+                  for k in range(6)]
+
+    def bwd_call(shp):
+        fm.fine_backward(shp, -1, inp.d_out, x_perm, y_perm, act_save, inp.w_gate, inp.w_up, inp.w_down, sb.row_of_pair,
                          sb.pair_of_row, sb.seg_off, topk_w, d_x, d_topk_w, d_wg, d_wu, d_wd, False, ws_bwd)
+
+    def st_backward():
+        for k in (1, 2, 3):
+            bwd_call(bwd_shapes[k])
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); bwd_call(bwd_shapes[4]); b.record()
+        wgrad_events.append((a, b))
+        bwd_call(bwd_shapes[5])
 
     stages = [("topk", st_topk), ("sched", st_sched), ("permute", st_permute), ("ffn", st_ffn), ("combine", st_combine)]
     if do_bwd:
@@ -182,7 +227,7 @@ def main():
         for _, fn in stages:
             fn()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     run_step = step
@@ -200,12 +245,14 @@ def main():
         for _ in range(3):
             run_step()
         torch.cuda.synchronize()
+    wgrad_events.clear()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    wgrad_ms = float(np.mean([a.elapsed_time(b) for a, b in wgrad_events])) if wgrad_events else None
     fwd_flop = 6.0 * s.P * s.d * s.f
     step_flop = fwd_flop * (3.0 if do_bwd else 1.0)
     value = step_flop / (ms_per_step * 1e-3) / 1e12
@@ -222,6 +269,9 @@ def main():
 
     it = args.detail_iters
     stage_ms = {name: float(np.median(time_ms(fn, it))) for name, fn in stages}
+    if do_bwd:
+        for k, name in ((1, "bwd_combine"), (2, "bwd_dh_swiglu"), (3, "bwd_dx"), (4, "bwd_wgrad"), (5, "bwd_permute")):
+            stage_ms[name] = float(np.median(time_ms(lambda k=k: bwd_call(bwd_shapes[k]), it)))
     if args.ffn == "per_rank" and args.also_fused:
         stage_ms["ffn_fused_call"] = float(np.median(time_ms(lambda: st_ffn_rank(-1), it)))
     rank_ms = [float(np.median(time_ms(lambda r=r: st_ffn_rank(r), it))) for r in range(s.G)]
@@ -232,7 +282,7 @@ def main():
     only1 = fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | fm.FLAG_ONLY_GEMM1)
     none = fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | fm.FLAG_ONLY_GEMM1 | fm.FLAG_ONLY_GEMM2)
     roofline = None
-    if cfg.dtype == "bf16":
+    if cfg.dtype == "bf16" and (not do_bwd or args.detail_iters > 0):
         only2 = fm.Shape(s.T, s.d, s.f, s.E, s.K, s.G, s.dtype, s.flags | fm.FLAG_ONLY_GEMM2)
 
         def sweep_ms(first, iters):
@@ -260,6 +310,21 @@ def main():
                     "traffic_unit": "bytes leaving the L2s per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
                                     "factors from the 1 GiB copy calibration; see profiles/)",
                     "avg_launch_ms": round(dur_ms, 4), "flops_per_launch": flops_per_launch}
+    gemm1_roofline = roofline
+    if do_bwd and wgrad_ms and not args.graph:
+        # the dominant kernel of the training step: the three weight-gradient GEMMs of every expert in one
+        # launch per step; 6 d f FLOP per row of the permuted buffer, P rows per launch; duration = mean
+        # over the timed steps (events around the launch, on the launch stream)
+        flops_per_launch = 6.0 * s.P * s.d * s.f
+        achieved = flops_per_launch / (wgrad_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "kernel": "k_wgrad_w8 (dWg, dWu, dWd of every expert), one launch per step",
+                    "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+                    "traffic": WGRAD_TRAFFIC_BYTES.get(cfg.name),
+                    "traffic_unit": "bytes leaving the L2s per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
+                                    "factors from the 1 GiB copy calibration; see profiles/)",
+                    "avg_launch_ms": round(wgrad_ms, 4), "flops_per_launch": flops_per_launch,
+                    "timed": "HIP events around the launch in each of the %d timed steps" % steps}
 
     es = 4 if cfg.dtype == "f32" else 2
     ffn_ms_total = float(np.sum(rank_ms))
@@ -282,10 +347,19 @@ def main():
         "rank_ffn_ms": [round(v, 4) for v in rank_ms],
         "input_gen_s": round(t_gen, 2),
     }
+    if do_bwd:
+        detail["gemm1_roofline"] = gemm1_roofline
+    # max/mean rank load: rows (what the scheduler balances), expert time (what a rank waits for) and the
+    # experts a rank touches (what its weight traffic follows), under the canonical schedule
+    seg_len = np.diff(sb.seg_off.cpu().numpy().astype(np.int64), axis=1)
+    rank_load = {"rows_max_over_mean": round(float(rank_rows.max() / rank_rows.mean()), 4),
+                 "expert_time_max_over_mean": round(max(rank_ms) / (ffn_ms_total / s.G), 4),
+                 "experts_per_rank": [int(v) for v in (seg_len > 0).sum(axis=1)],
+                 "placement": placement_note}
 
     # ---- the same per-rank calls under a restricted placement built from the loads (2 or so replica
     # slots per rank, the regime the paper runs in): every rank then holds the same number of experts
-    if args.placement == "full" and cfg.dtype == "bf16":
+    if restricted and args.placement == "full" and cfg.dtype == "bf16":
         mask, note = searched_placement()
         sb.run(s, topk_idx, mask)
         st_permute()
@@ -296,32 +370,39 @@ def main():
             "rank_ffn_ms_max_over_mean": round(max(rank_ms_r) / (sum(rank_ms_r) / s.G), 4),
             "rank_rows_max_over_mean": round(float(rows_r.max() / rows_r.mean()), 4),
             "ffn_TFLOPs_per_rank_calls": round(fwd_flop / (sum(rank_ms_r) * 1e-3) / 1e12, 2),
+            "experts_per_rank": [int(v) for v in (np.diff(sb.seg_off.cpu().numpy().astype(np.int64), axis=1) > 0).sum(axis=1)],
             "rank_ffn_ms": [round(v, 4) for v in rank_ms_r]}
+        rank_load["restricted_placement"] = {
+            "rows_max_over_mean": detail["restricted_placement"]["rank_rows_max_over_mean"],
+            "expert_time_max_over_mean": detail["restricted_placement"]["rank_ffn_ms_max_over_mean"]}
         sb.run(s, topk_idx, None)                    # back to the full placement
         st_permute()
 
     cpu_baseline = None
-    if not args.no_cpu_baseline:
-        cpu_baseline = run_cpu_baseline(cfg, inp, topk_idx, topk_w)
+    if cpu:
+        cpu_baseline = run_cpu_baseline(cfg, inp, topk_idx, topk_w, do_bwd)
 
     line = {
-        "metric": "MoE layer TFLOP/s per GPU (gate top-K + sched + permute + grouped GEMM + combine%s)" % (
-            " + backward" if do_bwd else ""),
-        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": BASELINE_METRIC,
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": s.T, "d": s.d, "f": s.f, "E": s.E, "K": s.K, "G": s.G,
+                   "step": "gate top-K + sched + permute + grouped GEMM (one call per rank) + combine%s" % (
+                       " + backward (dgrad, wgrad, gradient of combine weights)" if do_bwd else ""),
+                   "flop_per_step": step_flop,
                    "placement": placement_note, "ffn_calls": args.ffn, "launch": "HIP graph replay" if args.graph else "eager", "backward": bool(do_bwd),
                    "pre_activations": (None if not do_bwd else "recomputed" if args.recompute else "saved by the forward pass")},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "detail": detail,
+        "rank_load": rank_load, "roofline": roofline, "cpu_baseline": cpu_baseline, "detail": detail,
     }
-    print(json.dumps(line))
+    return line
 
 
-def run_cpu_baseline(cfg, inp, topk_idx, topk_w):
+def run_cpu_baseline(cfg, inp, topk_idx, topk_w, with_backward):
     """The CPU oracle as it stands, timed on a bounded sample of the same workload: the
-    scheduler on the full routing table, and the dense per-token layer (fp64) on the
-    first n tokens, n sized for roughly 10-30 s of host work."""
+    scheduler on the full routing table, and the dense per-token layer (fp64; with its
+    closed-form gradients when the step has a backward pass) on the first n tokens, n sized
+    for roughly 10-30 s of host work."""
     import numpy as np
     import torch
 
@@ -333,8 +414,10 @@ def run_cpu_baseline(cfg, inp, topk_idx, topk_w):
     t0 = time.perf_counter()
     sched.schedule(idx, cfg.E, cfg.G)
     t_sched = time.perf_counter() - t0
-    per_token = 6.0 * cfg.K * cfg.d * cfg.f
-    n = int(min(cfg.T, max(16, 5e12 // per_token)))
+    # FLOP the step is credited with per token (6 K d f forward, 18 with the backward pass); the oracle's
+    # gradient routine recomputes the forward quantities, so it executes 24 for 18
+    per_token = (18.0 if with_backward else 6.0) * cfg.K * cfg.d * cfg.f
+    n = int(min(cfg.T, max(16, (3.5e12 if with_backward else 5e12) // per_token)))
     tokens = np.arange(n)
     x64 = inp.x[:n].double().cpu().numpy()
     x_full = np.zeros((cfg.T, cfg.d))
@@ -346,12 +429,14 @@ def run_cpu_baseline(cfg, inp, topk_idx, topk_w):
 
     t0 = time.perf_counter()
     moe.dense_reference_by_expert(x_full, idx, w, weights_of, tokens=tokens)
+    if with_backward:
+        moe.backward_dense(x64, idx[:n], w[:n], weights_of, inp.d_out[:n].double().cpu().numpy())
     t_ffn = time.perf_counter() - t0
     flops = per_token * n
     return {"value": round(flops / t_ffn / 1e12, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "dense per-token fp64 layer on the first %d of %d tokens (%.2f s, includes fp64 weight "
+            "sample": "dense per-token fp64 layer%s on the first %d of %d tokens (%.2f s, includes fp64 weight "
                       "conversion); scheduler oracle on the full routing table took %.2f s"
-                      % (n, cfg.T, t_ffn, t_sched)}
+                      % (" and its closed-form gradients" if with_backward else "", n, cfg.T, t_ffn, t_sched)}
 
 
 INT32_VECTOR_PEAK_TOPS = 39.3       # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz: one 32-bit integer operation per lane and clock

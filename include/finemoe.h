@@ -15,7 +15,8 @@
  *   - Every array pointer is a DEVICE pointer on the current HIP device unless its name
  *     ends in _host.  The caller owns every buffer; the library allocates no device
  *     memory and keeps no state between calls.  Scratch comes from `ws`, whose size is
- *     given by fine_workspace_bytes(); `ws` must be 256-byte aligned.
+ *     given by fine_workspace_bytes(); `ws` must be 256-byte aligned (else FINE_INVALID_ARG), other
+ *     buffers 16-byte aligned.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work on that stream and never synchronise the device.
  *   - Outputs are fully overwritten, except the weight-gradient buffers of
@@ -48,14 +49,10 @@ enum {
 
 enum { FINE_F32 = 0, FINE_BF16 = 1 };
 
-/* flags */
+/* flags (fine_shape.flags).  Other bits are measurement and test switches declared in
+ * finemoe_measure.h; they are not part of this contract and are zero in normal use. */
 enum {
-    FINE_FLAG_LOCALITY = 1,      /* run the local pass of Algorithm 1 first: a rank keeps its own tokens up to its replica load */
-    FINE_FLAG_SIMPLE_FFN = 2,    /* debugging: plain tiled FMA kernels instead of MFMA */
-    FINE_FLAG_ONLY_GEMM1 = 4,    /* measurement: fine_grouped_ffn runs only X[Wg|Wu] + SwiGLU   */
-    FINE_FLAG_ONLY_GEMM2 = 8,    /* measurement: fine_grouped_ffn runs only H Wd (H from ws)     */
-    FINE_FLAG_TILE_SHIFT = 8,    /* bits 8-9: row tile of the MFMA kernels, 0 = chosen from the */
-    FINE_FLAG_TILE_MASK = 0x300  /*   shape, 1 = 64 rows, 2 = 128 rows, 3 = 256 rows           */
+    FINE_FLAG_LOCALITY = 1       /* run the local pass of Algorithm 1 first: a rank keeps its own tokens up to its replica load */
 };
 
 /* which entry point a workspace is for */
@@ -83,8 +80,8 @@ size_t fine_workspace_bytes(const fine_shape* shape, int which);
  * topk_w[t][:] = softmax over those K logits (fp32).
  *   x [T,d] dtype, w_router [d,E] dtype, bias [E] fp32 or NULL,
  *   topk_idx [T,K] int32 out, topk_w [T,K] fp32 out.
- *   ws: NULL, or fine_workspace_bytes(shape, FINE_WS_TOPK) bytes of device scratch, 16-byte
- *   aligned.  With it, bf16 layers of more than 64 experts and few tokens split the sum over i
+ *   ws: NULL, or fine_workspace_bytes(shape, FINE_WS_TOPK) bytes of device scratch (256-byte
+ *   aligned like every workspace).  With it, bf16 layers of more than 64 experts and few tokens split the sum over i
  *   among several thread blocks per token tile (partial logits in ws, added in ascending order of
  *   i by a second kernel); the result is the same up to fp32 summation order.  Calls that may
  *   overlap on the GPU need a workspace each.

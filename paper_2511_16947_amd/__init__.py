@@ -26,7 +26,10 @@ FINE_WORKSPACE_TOO_SMALL = -3
 FINE_INFEASIBLE = -4
 FINE_HIP_ERROR = -5
 FINE_F32, FINE_BF16 = 0, 1
-FLAG_LOCALITY, FLAG_SIMPLE_FFN, FLAG_ONLY_GEMM1, FLAG_ONLY_GEMM2 = 1, 2, 4, 8
+FLAG_LOCALITY = 1
+# measurement and test switches (include/finemoe_measure.h; not part of the contract)
+FLAG_SIMPLE_FFN, FLAG_ONLY_GEMM1, FLAG_ONLY_GEMM2 = 2, 4, 8
+FLAG_TILE_SHIFT, FLAG_BWD_STAGE_SHIFT = 8, 12
 WS_TOPK, WS_SCHED, WS_FFN, WS_BACKWARD = 0, 1, 2, 3
 
 EXPORTS = ["fine_version", "fine_last_hip_error", "fine_workspace_bytes", "fine_topk", "fine_sched",

@@ -8,6 +8,7 @@ thread_local int g_last_hip_error = 0;
 namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }      // workspaces
 
 int check_shape(const fine_shape* s) {
     if (s == nullptr) return FINE_INVALID_ARG;
@@ -74,7 +75,7 @@ int fine_topk(const fine_shape* shape, const void* x, const void* w_router, cons
               int32_t* topk_idx, float* topk_w, void* ws, size_t ws_bytes, void* stream) {
     FINE_TRY(check_shape(shape));
     if (!x || !w_router || !topk_idx || !topk_w) return FINE_INVALID_ARG;
-    if (ws && !aligned16(ws)) return FINE_INVALID_ARG;
+    if (ws && !aligned256(ws)) return FINE_INVALID_ARG;
     return launch_topk(*shape, x, w_router, bias, topk_idx, topk_w, ws, ws ? ws_bytes : 0, (hipStream_t)stream);
 }
 
@@ -86,7 +87,7 @@ int fine_sched_warm(const fine_shape* shape, const int32_t* topk_idx, const uint
     if (!topk_idx || !load || !input_eg || !x_eg || !max_load || !pair_dst || !row_of_pair || !pair_of_row ||
         !seg_off || !rank_off || !ws)
         return FINE_INVALID_ARG;
-    if (!aligned16(ws)) return FINE_INVALID_ARG;
+    if (!aligned256(ws)) return FINE_INVALID_ARG;
     if (ws_bytes < sched_ws_layout(*shape).total) return FINE_WORKSPACE_TOO_SMALL;
     if (shape->T == 0) return FINE_INVALID_ARG;
     return launch_sched(*shape, topk_idx, place, x_prev, load, input_eg, x_eg, max_load, pair_dst, row_of_pair,
@@ -132,7 +133,7 @@ int fine_grouped_ffn(const fine_shape* shape, int32_t rank, const void* x_perm, 
     if (!x_perm || !w_gate || !w_up || !w_down || !seg_off || !y_perm || !ws) return FINE_INVALID_ARG;
     if (rank < -1 || rank >= shape->G) return FINE_INVALID_ARG;
     if (!aligned16(x_perm) || !aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down) || !aligned16(y_perm) ||
-        !aligned16(ws) || (act_save && !aligned16(act_save)))
+        !aligned256(ws) || (act_save && !aligned16(act_save)))
         return FINE_INVALID_ARG;
     if (ws_bytes < ffn_ws_layout(*shape).total) return FINE_WORKSPACE_TOO_SMALL;
     const int lo = rank < 0 ? 0 : rank, hi = rank < 0 ? shape->G : rank + 1;
@@ -165,7 +166,7 @@ int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
     if (rank < -1 || rank >= shape->G) return FINE_INVALID_ARG;
     if (!aligned16(d_out) || !aligned16(x_perm) || !aligned16(y_perm) || !aligned16(w_gate) || !aligned16(w_up) ||
         !aligned16(w_down) || !aligned16(d_x) || !aligned16(d_w_gate) || !aligned16(d_w_up) || !aligned16(d_w_down) ||
-        !aligned16(ws) || (act_save && !aligned16(act_save)))
+        !aligned256(ws) || (act_save && !aligned16(act_save)))
         return FINE_INVALID_ARG;
     if (ws_bytes < bwd_ws_layout(*shape).total) return FINE_WORKSPACE_TOO_SMALL;
     const int lo = rank < 0 ? 0 : rank, hi = rank < 0 ? shape->G : rank + 1;

@@ -285,9 +285,9 @@ __global__ __launch_bounds__(512) void k_wgrad_w8(WgradProblem p0, WgradProblem 
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 int run_dgrad(const fine_shape& s, int rank_lo, int rank_hi, const uint16_t* dy, const uint16_t* act, const uint16_t* wg, const uint16_t* wu,
               const uint16_t* wd, const int32_t* seg_off, uint16_t* dact, uint16_t* h, uint16_t* dxp,
-              TileEntry* tiles, int32_t* count, int max_tiles, hipStream_t st) {
+              TileEntry* tiles, int32_t* count, int max_tiles, bool run_dh, bool run_dx, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
-    FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
+    if (run_dh) FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
     const size_t lds = (size_t)2 * (BM + BN) * 128;
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
     constexpr int threads = WAVES_M * WAVES_N * 64;
@@ -297,10 +297,14 @@ int run_dgrad(const fine_shape& s, int rank_lo, int rank_hi, const uint16_t* dy,
     FINE_TRY(raise_lds_limit((const void*)k1, (int)lds, lds_set1));
     FINE_TRY(raise_lds_limit((const void*)k2, (int)lds, lds_set2));
     const int grid = 256 * ((lds <= 80 * 1024) ? 2 : 1);
-    hipLaunchKernelGGL(k1, dim3(grid), dim3(threads), lds, st, dy, wd, act, s.d, s.f, dact, h, tiles, count);
-    FINE_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k2, dim3(grid), dim3(threads), lds, st, dact, wg, wu, s.d, s.f, dxp, tiles, count);
-    FINE_LAUNCH_CHECK();
+    if (run_dh) {
+        hipLaunchKernelGGL(k1, dim3(grid), dim3(threads), lds, st, dy, wd, act, s.d, s.f, dact, h, tiles, count);
+        FINE_LAUNCH_CHECK();
+    }
+    if (run_dx) {
+        hipLaunchKernelGGL(k2, dim3(grid), dim3(threads), lds, st, dact, wg, wu, s.d, s.f, dxp, tiles, count);
+        FINE_LAUNCH_CHECK();
+    }
     return FINE_OK;
 }
 
@@ -344,11 +348,15 @@ int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d
     // in the workspace, and the call for the last rank gathers d_x from the rows of all ranks.
     const bool one_rank = rank_hi - rank_lo < s.G;
     const int32_t* rank_rows = one_rank ? seg_off + (size_t)rank_lo * (s.E + 1) : nullptr;
-    FINE_TRY(launch_combine_bwd(s, d_out, y_perm, pair_of_row, topk_w, dy, d_topk_w, rank_rows, st));
+    // measurement: only one of the stages (they must then be called in order 1 .. 5 on one workspace)
+    const int only = (s.flags & FINE_MEASURE_BWD_STAGE_MASK) >> FINE_MEASURE_BWD_STAGE_SHIFT;
+    auto on = [&](int stage) { return only == 0 || only == stage; };
+    if (on(1)) FINE_TRY(launch_combine_bwd(s, d_out, y_perm, pair_of_row, topk_w, dy, d_topk_w, rank_rows, st));
     if (act == nullptr) {      // recompute the pre-activations A | B
         auto* act_ws = reinterpret_cast<uint16_t*>(ws + L.act);
-        FINE_TRY(launch_ffn_parts(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h, nullptr, act_ws, tiles, count, L.max_tiles,
-                                  reinterpret_cast<float*>(ws + L.sk), true, false, st));
+        if (on(1))
+            FINE_TRY(launch_ffn_parts(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h, nullptr, act_ws, tiles, count,
+                                      L.max_tiles, reinterpret_cast<float*>(ws + L.sk), true, false, st));
         act = act_ws;
     }
     const double P = (double)s.T * s.K;
@@ -356,18 +364,23 @@ int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d
     int tile = (s.flags & FINE_FLAG_TILE_MASK) >> FINE_FLAG_TILE_SHIFT;
     if (tile == 0) tile = seg_rows >= 384.0 ? 3 : (seg_rows >= 96.0 ? 2 : 1);
 #define FINE_DGRAD(WAM, WAN, WMM, WNN)                                                                        \
-    FINE_TRY((run_dgrad<WAM, WAN, WMM, WNN>(s, rank_lo, rank_hi, dy, act, (const uint16_t*)wg, (const uint16_t*)wu, (const uint16_t*)wd, \
-                                            seg_off, dact, h, dxp, tiles, count, L.max_tiles, st)))
-    if (tile == 3) FINE_DGRAD(2, 4, 4, 2);
-    else if (tile == 2) FINE_DGRAD(2, 2, 2, 4);
-    else FINE_DGRAD(1, 4, 2, 2);
+    FINE_TRY((run_dgrad<WAM, WAN, WMM, WNN>(s, rank_lo, rank_hi, dy, act, (const uint16_t*)wg, (const uint16_t*)wu, \
+                                            (const uint16_t*)wd, seg_off, dact, h, dxp, tiles, count, L.max_tiles,  \
+                                            on(2), on(3), st)))
+    if (on(2) || on(3)) {
+        if (tile == 3) FINE_DGRAD(2, 4, 4, 2);
+        else if (tile == 2) FINE_DGRAD(2, 2, 2, 4);
+        else FINE_DGRAD(1, 4, 2, 2);
+    }
 #undef FINE_DGRAD
     // weight-gradient tiles span the weight matrices, not the segments
-    if (s.d >= 256 && s.f >= 256 && tile != 1)
-        FINE_TRY((run_wgrad<2, 4, 4, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
-    else
-        FINE_TRY((run_wgrad<2, 2, 2, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
-    if (rank_hi == s.G) FINE_TRY(launch_permute_bwd(s, dxp, row_of_pair, d_x, st));
+    if (on(4)) {
+        if (s.d >= 256 && s.f >= 256 && tile != 1)
+            FINE_TRY((run_wgrad<2, 4, 4, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+        else
+            FINE_TRY((run_wgrad<2, 2, 2, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+    }
+    if (on(5) && rank_hi == s.G) FINE_TRY(launch_permute_bwd(s, dxp, row_of_pair, d_x, st));
     return FINE_OK;
 }
 

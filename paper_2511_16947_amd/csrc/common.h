@@ -9,6 +9,7 @@
 #include <atomic>
 
 #include "../../include/finemoe.h"
+#include "../../include/finemoe_measure.h"
 
 namespace fine {
 
