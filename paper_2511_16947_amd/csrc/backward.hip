@@ -27,8 +27,10 @@ __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, con
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int ntn = (f + BN - 1) / BN, ntm = *count, total = ntm * ntn;
     for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
-        const TileEntry te = tiles[work % ntm];
-        const int n0 = (work / ntm) * BN;
+        int tm, tn;
+        tile_of_work(work, ntm, ntn, tm, tn);
+        const TileEntry te = tiles[tm];
+        const int n0 = tn * BN;
         const uint16_t* W = wd + (size_t)te.expert * f * d;
         f32x16 acc[WM][WN];
         zero_acc<WM, WN>(acc);
@@ -136,8 +138,10 @@ __device__ __forceinline__ void bwd_dx_body(const uint16_t* __restrict__ dact, c
     const int ntn = (d + BN - 1) / BN, ntm = *count, total = ntm * ntn;
     const int nkf = f / BK;
     for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
-        const TileEntry te = tiles[work % ntm];
-        const int n0 = (work / ntm) * BN;
+        int tm, tn;
+        tile_of_work(work, ntm, ntn, tm, tn);
+        const TileEntry te = tiles[tm];
+        const int n0 = tn * BN;
         const uint16_t* Wg = wg + (size_t)te.expert * d * f;
         const uint16_t* Wu = wu + (size_t)te.expert * d * f;
         // k runs over the f columns of dA with Wg_e, then over those of dB with Wu_e.  4 waves: the
@@ -217,8 +221,9 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
         WgradProblem p = p0;
         if (j >= t0 + t1) { p = p2; j -= t0 + t1; }
         else if (j >= t0) { p = p1; j -= t0; }
-        const int ntm = cdiv_dev(p.M, BM);
-        const int m0 = (j % ntm) * BM, n0 = (j / ntm) * BN;
+        int tm, tn;
+        tile_of_work(j, cdiv_dev(p.M, BM), cdiv_dev(p.N, BN), tm, tn);
+        const int m0 = tm * BM, n0 = tn * BN;
         // k-tiles: 64 rows at a time through the expert's segment on every rank of [g_lo, g_hi), ascending
         int nk = 0;
         for (int g = g_lo; g < g_hi; ++g)
@@ -244,7 +249,10 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
             DmaOperand<WN> ob;
             ob.init(p.B, p.B, [&](int pn, int c) { return min(n0 + 128 * pn + 8 * c, p.N - 8); }, (size_t)p.ldb,
                     [&](int f) { return 64 * wn + 32 * f; });
-            k_loop8(nk, smem, acc, oa, ob, k_tile);
+            k_loop8<false, 4, true>(nk, smem, acc, oa, ob, k_tile);      // operands in natural order
+            store_tile_f32_direct<WAVES_M, WAVES_N, WM, WN>(acc, p.out + (size_t)e * p.M * p.N, p.M, p.N, m0, n0,
+                                                            accumulate != 0);
+            continue;
         } else {
             LoaderMC<BM, true> la;
             la.init([&](int r8) { return p.A + min(m0 + 8 * r8, p.M - 8); }, (size_t)p.lda);
@@ -335,6 +343,7 @@ int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d
                     const float* topk_w, void* d_x, float* d_topk_w, float* d_wg, float* d_wu,
                     float* d_wd, int accumulate, char* ws, hipStream_t st) {
     if (s.dtype != FINE_BF16) return FINE_UNSUPPORTED;
+    if (s.d > (1 << 20) || s.f > (1 << 20)) return FINE_UNSUPPORTED;      // byte offsets inside a 256-row tile stay in 32 bits
     const BwdWs L = bwd_ws_layout(s);
     auto* dy = reinterpret_cast<uint16_t*>(ws + L.dy);
     auto* dact = reinterpret_cast<uint16_t*>(ws + L.dact);

@@ -45,8 +45,10 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
 
     // acc += (rows of tile `work`) x (its weight columns) over k-tiles [kb, kb + kn)
     auto run_tile = [&](int work, int kb, int kn) {
-        const TileEntry te = tiles[work % ntm];
-        const int n0 = (work / ntm) * BNC;
+        int tm, tn;
+        tile_of_work(work, ntm, ntn, tm, tn);
+        const TileEntry te = tiles[tm];
+        const int n0 = tn * BNC;
         const uint16_t* Bg = B0 + (size_t)te.expert * b_expert_stride;
         const uint16_t* Bu = (EPI == 0) ? B1 + (size_t)te.expert * b_expert_stride : nullptr;
         auto a_row = [&](int r) { return (size_t)min(r, te.rows - 1) * lda; };
@@ -92,8 +94,10 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
 
     // LDS-staged epilogue of tile `work`, 8-byte coalesced stores
     auto epilogue = [&](int work) {
-        const TileEntry te = tiles[work % ntm];
-        const int n0 = (work / ntm) * BNC;
+        int tm, tn;
+        tile_of_work(work, ntm, ntn, tm, tn);
+        const TileEntry te = tiles[tm];
+        const int n0 = tn * BNC;
         constexpr int WMC = (BM * (BNC * 2 + 8) <= 2 * (BM + BN) * 128) ? WM : WM / 2;
         if constexpr (EPI == 0) {
             if (act != nullptr) {

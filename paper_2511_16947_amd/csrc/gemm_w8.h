@@ -283,7 +283,9 @@ struct Frags {
 //                     no side operations, and the barrier waits for everything outstanding
 //   nf                (RAGGED_M only) how many of the wave's four 32-row fragments hold valid rows:
 //                     MFMAs and fragment reads of the others are skipped
-template <int P, bool BARRIER, bool RAGGED_M, int RING, bool ISSUE, int WM, typename OA, typename OB>
+//   NATURAL           MFMA operands in their natural order (accumulator tiles hold the output tile as it
+//                     lies, see store_tile_f32_direct) instead of swapped (transposed tiles)
+template <int P, bool BARRIER, bool RAGGED_M, int RING, bool ISSUE, int WM, bool NATURAL, typename OA, typename OB>
 __device__ inline void half_step8(const char* a_src, const char* b_src, const char* a_next, const char* b_next,
                                   char* a_dst, char* b_dst, f32x16 (&acc)[WM][2], Frags<WM>& f0, Frags<WM>& f1, OA& oa,
                                   OB& ob, ptrdiff_t ka, ptrdiff_t kb, int kbase, int kend, int ksel, int nf) {
@@ -306,7 +308,10 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
             constexpr int m = 2 * j.value + t.value;
             constexpr int mi = m / WN, ni = m % WN;
             if (RAGGED_M && mi >= nf) return;
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[mi][ni], 0, 0, 0);
+            if constexpr (NATURAL)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[mi], f.b[ni], acc[mi][ni], 0, 0, 0);
+            else
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[ni], f.a[mi], acc[mi][ni], 0, 0, 0);
         });
     };
     // Fragment reads are spread over the slots (B fragments in slot 0, A fragments in slots 1
@@ -358,7 +363,7 @@ __device__ inline void half_step8(const char* a_src, const char* b_src, const ch
 // RAGGED_M: the wave computes only its first nf 32-row fragments (a row tile at the end of a
 // segment); the tile is still loaded whole.
 // RING: stages of a ring operand's ring (4 or 5; operand A's ring always has 4).
-template <bool RAGGED_M = false, int RING = 4, int WM, typename OA, typename OB, typename Tile>
+template <bool RAGGED_M = false, int RING = 4, bool NATURAL = false, int WM, typename OA, typename OB, typename Tile>
 __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[WM][2], OA& oa, OB& ob, Tile tile, int nf = WM) {
     constexpr int kA = OA::kKind, kB = OB::kKind;
     constexpr bool kAnyRing = kA == kRing || kB == kRing;
@@ -423,11 +428,11 @@ __device__ inline void k_loop8(int nk, char* smem, f32x16 (&acc)[WM][2], OA& oa,
         const int h = 2 * kt;
         const KTile& d0 = (RING == 4) ? n1 : n2;      // ring, P = 0
         constexpr int d0_half = (RING == 4) ? 32 : 0, d1_half = (RING == 4) ? 0 : 32;
-        half_step8<0, kAnyRing, RAGGED_M, RING, issue0.value, WM>(
+        half_step8<0, kAnyRing, RAGGED_M, RING, issue0.value, WM, NATURAL>(
             a_at(kt, h), b_at(kt, h), a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + RING - 1),
             b_at(kt + 1, h + RING - 1), acc, f0, f1, oa, ob, kA == kRing ? d0.a + d0_half : n2.a,
             kB == kRing ? d0.b + d0_half : n2.b, d0.base, d0.end, 0, nf);
-        half_step8<1, true, RAGGED_M, RING, issue1.value, WM>(
+        half_step8<1, true, RAGGED_M, RING, issue1.value, WM, NATURAL>(
             a_at(kt, h + 1), b_at(kt, h + 1), a_at(kt + 1, h + 2), b_at(kt + 1, h + 2),
             kA == kRow ? a_at(kt, 0) : a_at(kt + 1, h + RING), kB == kRow ? b_at(kt, 0) : b_at(kt + 1, h + RING), acc, f0,
             f1, oa, ob, kA == kRing ? n2.a + d1_half : n2.a, kB == kRing ? n2.b + d1_half : n2.b, n2.base, n2.end, n2.sel, nf);

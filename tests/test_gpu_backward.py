@@ -41,6 +41,9 @@ def small_train_cfgs():
         # one long segment per expert (K = 1, two experts, one rank): whole 256-row tiles and a ragged
         # tail in the data-gradient kernels, a long contraction in the weight gradients
         wl.scaled(c5, name="cfg5_long", T=1200, d=128, f=192, E=8, K=1, G=1, bias_kind="one_hot", bias_scale=3.0),
+        # weight matrices of 320 x 448: the 8-wave weight-gradient kernel (256 x 256 tiles stored straight from
+        # the accumulators) with ragged last row and column tiles
+        wl.scaled(c5, name="cfg5_wgrad_ragged", T=1024, d=320, f=448, E=4, K=2, G=2, bias_kind="scaled_z", bias_scale=1.0),
     ]
 
 
@@ -70,11 +73,12 @@ def test_backward_elementwise(cfg, tile, saved):
             else:
                 assert not got[e].any(), (key, e)          # experts without tokens: exact zeros
 
-    if tile == 0 and not saved:
+    if tile in (0, 3) and not saved:
         # accumulate adds to what is there
         before = bwd.d_wd.clone()
         bwd.run(accumulate=True)
         assert max_rel_err(to64(bwd.d_wd), 2.0 * to64(before)) <= 1e-6
+        assert max_rel_err_rows(to64(bwd.d_wd).reshape(-1, cfg.d), 2.0 * to64(before).reshape(-1, cfg.d)) <= 1e-6
 
 
 @pytest.mark.parametrize("tile", [0, 3])
