@@ -257,37 +257,46 @@ def replica_loads_full(load: np.ndarray, G: int):
 # --------------------------------------------------------------------------
 
 def algorithm1(input_eg: np.ndarray, x: np.ndarray, place: np.ndarray, locality: bool = True):
-    """Range-based routing of tokens to replicas.
+    """Range-based routing of tokens to replicas (Algorithm 1).
 
-    Returns (Y, routes): Y[e][g][g'] = number of expert-e tokens of source rank
-    g computed on rank g'; routes[e][g] = the (g', y) hand-outs of source g in
-    the order the algorithm makes them (y > 0 only)."""
+    For every expert the tokens of the source ranks, in ascending rank order, form one queue and
+    the loads of its replicas, in ascending rank order, another.  Routing pairs the heads of the
+    two queues: the amount that both can take is handed over, and whichever head is used up steps
+    forward.  Before that, with `locality`, a rank that is both source and replica keeps
+    min(its tokens, its load) to itself.
+
+    Returns (Y, routes): Y[e][g][g'] = number of expert-e tokens of source rank g computed on rank
+    g'; routes[e][g] = the (g', amount) hand-outs of source g in the order they are made."""
     E, G = place.shape
-    remain_input = np.array(input_eg, dtype=np.int64)
-    remain_x = np.array(x, dtype=np.int64)
     Y = np.zeros((E, G, G), dtype=np.int64)
     routes = [[[] for _ in range(G)] for _ in range(E)]
     for e in range(E):
-        edp = [g for g in range(G) if place[e, g]]
+        waiting = [int(v) for v in input_eg[e]]          # tokens of each source not routed yet
+        room = [int(x[e, g]) if place[e, g] else 0 for g in range(G)]
+        assert all(int(x[e, g]) == 0 for g in range(G) if not place[e, g])
+        replicas = [g for g in range(G) if place[e, g]]
         if locality:
-            # first, local tokens to local replicas
-            for g in edp:
-                y = int(min(remain_input[e, g], remain_x[e, g]))
-                if y > 0:
-                    Y[e, g, g] += y
-                    routes[e][g].append((g, y))
-                remain_input[e, g] -= y
-                remain_x[e, g] -= y
-        # then, global tokens to global replicas
-        for g in range(G):
-            for g2 in edp:
-                y = int(min(remain_input[e, g], remain_x[e, g2]))
-                if y > 0:
-                    Y[e, g, g2] += y
-                    routes[e][g].append((g2, y))
-                remain_input[e, g] -= y
-                remain_x[e, g2] -= y
-    assert not remain_input.any() and not remain_x.any()
+            for g in replicas:
+                kept = min(waiting[g], room[g])
+                if kept > 0:
+                    Y[e, g, g] += kept
+                    routes[e][g].append((g, kept))
+                    waiting[g] -= kept
+                    room[g] -= kept
+        src, rep = 0, 0                                   # heads of the two queues
+        while src < G and rep < len(replicas):
+            g, h = src, replicas[rep]
+            amount = min(waiting[g], room[h])
+            if amount > 0:
+                Y[e, g, h] += amount
+                routes[e][g].append((h, amount))
+                waiting[g] -= amount
+                room[h] -= amount
+            if waiting[g] == 0:
+                src += 1
+            else:
+                rep += 1
+        assert not any(waiting) and not any(room)
     return Y, routes
 
 
