@@ -142,6 +142,45 @@ int fine_sched_warm(const fine_shape* shape, const int32_t* topk_idx, const uint
                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Communication-aware token scheduling (Appendix A.1, Eq. 4): as fine_sched, but the replica loads
+ * minimise comp + alpha * comm, where comp is the largest rank load and comm the largest of all
+ * ranks' send and receive volumes,
+ *   send_g = sum_e max(input_e^g - x_e^g, 0),  recv_g = sum_e max(x_e^g - input_e^g, 0)
+ * over the experts with a replica on g (the printed sums with min(x, input), rewritten), and the
+ * routing prefers the same rank, then the same node, then any rank ("topology-aware scheduling").
+ *   alpha = alpha_num / alpha_den (alpha_num >= 0, alpha_den >= 1); alpha = 0 gives fine_sched's
+ *        replica loads (comm unbounded);
+ *   ranks_per_node: that many consecutive ranks form a node; 0 or 1: no pass inside nodes, i.e.
+ *        Algorithm 1 as in fine_sched;
+ *   place [E,G] uint8 or NULL = every expert on every rank;
+ *   comp_comm [2] int32 out: (C*, M*), the integer pair that minimises C + alpha M among all pairs
+ *        for which a schedule with comp <= C and comm <= M exists (equal values: the smaller C, then
+ *        the smaller M); M* = -1 when alpha = 0.  x_eg is the lexicographically greatest integer
+ *        schedule (e ascending, then g ascending) with comp <= C* and comm <= M*.  (-1, -1) and
+ *        fine_sched's outputs for "no schedule exists" when an expert with load has no replica.
+ *   The other arguments and outputs are fine_sched's.
+ * The paper solves its scheduling problems on the host between GPU stages and so does this entry
+ * point for the replica loads (exact integer flows; everything else runs in the scheduler's
+ * kernels): it copies E*G integers to the host and back and SYNCHRONISES `stream` twice, the one
+ * exception to the rule above; it cannot be captured in a graph and allocates host memory.
+ */
+int fine_sched_comm(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
+                    int32_t alpha_num, int32_t alpha_den, int32_t ranks_per_node,
+                    int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* comp_comm,
+                    int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+                    int32_t* seg_off, int32_t* rank_off, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The host part of fine_sched_comm by itself, on HOST arrays (no GPU is touched): the replica loads
+ * x_eg_host [E,G] and comp_comm_host [2] = (C*, M*) as described there, from load_host [E],
+ * input_eg_host [E,G] (rows must sum to load_host, else FINE_INVALID_ARG) and place_host [E,G]
+ * (non-zero = replica).  E <= 1024, G <= 64.
+ */
+int fine_comm_replica_loads_host(int32_t E, int32_t G, const int32_t* load_host, const int32_t* input_eg_host,
+                                 const uint8_t* place_host, int32_t alpha_num, int32_t alpha_den,
+                                 int32_t* x_eg_host, int32_t* comp_comm_host);
+
+/*
  * fine_sched for callers that cannot allocate or pass device scratch memory: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without ws) and
  * the same results, bit for bit, as fine_sched; the tables fine_sched keeps in `ws` live in a
@@ -214,6 +253,24 @@ int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
                   const float* topk_w,
                   void* d_x, float* d_topk_w, float* d_w_gate, float* d_w_up, float* d_w_down,
                   int accumulate, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Symmetric expert placement with two replicas per expert from a Cayley graph (Section 5.2,
+ * Appendix B; the FineEP parameter d = 2).  Only E and G of `shape` matter.  Ranks are the elements
+ * of Z_{n_1} x ... x Z_{n_k}: orders_host [n_factors] = (n_1, ..., n_k) with product G; the rank
+ * index is the mixed-radix number of the tuple, last factor fastest.  For a generator s every rank a
+ * has an edge to a + s, and every edge is an expert with its replicas on the two end points.
+ * gens_host [n_gens][n_factors] lists ONE generator of each pair {s, -s} (entries are taken modulo
+ * the orders; the identity is not allowed); a generator that is its own inverse gives each of its
+ * G/2 edges once.  `complete` complete graphs on all ranks come first (Example 4: complete graphs,
+ * then the remaining edges).  Experts are numbered: complete graphs (pairs a < b in lexicographic
+ * order), then generator by generator, rank a ascending.  The number of edges must be E, else
+ * FINE_INVALID_ARG.  n_factors <= 6, n_gens <= 64.   place [E,G] uint8 out (device).
+ * Appendix B's examples: 1: orders (8), gens (1);  2: orders (4,4), gens (0,1), (1,0);
+ * 3: orders (2,4), gens (0,1), (1,1);  4: complete = 1, orders (2,2,2), gens (0,0,1).
+ */
+int fine_cayley_placement(const fine_shape* shape, int32_t n_factors, const int32_t* orders_host, int32_t n_gens,
+                          const int32_t* gens_host, int32_t complete, uint8_t* place, void* stream);
 
 /*
  * Expert placement from known expert loads (Section 5.3), scored by Eq. 3 (Section 5.1).

@@ -112,3 +112,56 @@ def search(load, G: int, slots: int, n: int, seed: int):
         if best < 0 or m < scores[best]:
             best, best_place = c, place
     return counts, scores, best, best_place
+
+
+# --------------------------------------------------------------------------
+# symmetric placements from Cayley graphs (Appendix B)
+# --------------------------------------------------------------------------
+
+def cayley_placement(orders, gens, complete: int = 0) -> np.ndarray:
+    """Two replicas per expert on a Cayley graph (Appendix B; the FineEP parameter d = 2).
+
+    Ranks are the elements of Z_{n_1} x ... x Z_{n_k} (orders = (n_1, ..., n_k), their product
+    is G; the rank index is the mixed-radix number of the tuple, last factor fastest).  For
+    every generator s there is an edge between a and a + s, and an edge is an expert whose two
+    replicas sit on its end points.  `gens` lists one generator of each pair {s, -s}; a generator
+    that is its own inverse yields each edge once.  `complete` complete graphs on all ranks come
+    first (Example 4: "first generate a complete graph and then add the remaining edges").
+    Experts are numbered: complete graphs (pairs a < b in lexicographic order), then generator
+    by generator, rank a ascending."""
+    orders = [int(n) for n in orders]
+    G = 1
+    for n in orders:
+        G *= n
+
+    def to_tuple(a):
+        t = []
+        for n in reversed(orders):
+            t.append(a % n)
+            a //= n
+        return t[::-1]
+
+    def to_rank(t):
+        a = 0
+        for v, n in zip(t, orders):
+            a = a * n + v % n
+        return a
+
+    edges = []
+    for _ in range(complete):
+        edges += [(a, b) for a in range(G) for b in range(a + 1, G)]
+    for s in gens:
+        s = [int(v) % n for v, n in zip(s, orders)]
+        if not any(s):
+            raise ValueError("the identity is no generator")
+        own_inverse = all((2 * v) % n == 0 for v, n in zip(s, orders))
+        for a in range(G):
+            b = to_rank([u + v for u, v in zip(to_tuple(a), s)])
+            if own_inverse and b < a:
+                continue
+            edges.append((a, b))
+    place = np.zeros((len(edges), G), dtype=np.uint8)
+    for e, (a, b) in enumerate(edges):
+        place[e, a] = 1
+        place[e, b] = 1
+    return place

@@ -33,8 +33,8 @@ FLAG_TILE_SHIFT, FLAG_BWD_STAGE_SHIFT = 8, 12
 WS_TOPK, WS_SCHED, WS_FFN, WS_BACKWARD = 0, 1, 2, 3
 
 EXPORTS = ["fine_version", "fine_last_hip_error", "fine_workspace_bytes", "fine_topk", "fine_sched",
-           "fine_sched_warm", "fine_sched_static",
-           "fine_permute", "fine_grouped_ffn", "fine_combine", "fine_backward", "fine_replica_counts",
+           "fine_sched_warm", "fine_sched_static", "fine_sched_comm", "fine_comm_replica_loads_host",
+           "fine_permute", "fine_grouped_ffn", "fine_combine", "fine_backward", "fine_cayley_placement", "fine_replica_counts",
            "fine_eval_placements", "fine_place_search"]
 
 
@@ -78,6 +78,10 @@ def load_library() -> ctypes.CDLL:
     lib.fine_sched_warm.argtypes = [sp] + [vp] * 12 + [vp, sz, vp]
     lib.fine_sched_static.restype = ctypes.c_int
     lib.fine_sched_static.argtypes = [sp] + [vp] * 11 + [vp]
+    lib.fine_sched_comm.restype = ctypes.c_int
+    lib.fine_sched_comm.argtypes = [sp, vp, vp, i32, i32, i32] + [vp] * 9 + [vp, sz, vp]
+    lib.fine_comm_replica_loads_host.restype = ctypes.c_int
+    lib.fine_comm_replica_loads_host.argtypes = [i32, i32, vp, vp, vp, i32, i32, vp, vp]
     lib.fine_permute.restype = ctypes.c_int
     lib.fine_permute.argtypes = [sp, vp, vp, vp, vp]
     lib.fine_grouped_ffn.restype = ctypes.c_int
@@ -86,6 +90,8 @@ def load_library() -> ctypes.CDLL:
     lib.fine_combine.argtypes = [sp, vp, vp, vp, vp, vp]
     lib.fine_backward.restype = ctypes.c_int
     lib.fine_backward.argtypes = [sp, i32] + [vp] * 16 + [ctypes.c_int, vp, sz, vp]
+    lib.fine_cayley_placement.restype = ctypes.c_int
+    lib.fine_cayley_placement.argtypes = [sp, i32, vp, i32, vp, i32, vp, vp]
     lib.fine_replica_counts.restype = ctypes.c_int
     lib.fine_replica_counts.argtypes = [sp, vp, i32, vp, vp]
     lib.fine_eval_placements.restype = ctypes.c_int
@@ -185,6 +191,31 @@ def fine_sched_static(shape: Shape, topk_idx, place, load, input_eg, x_eg, max_l
     _check("fine_sched_static", rc)
 
 
+def fine_sched_comm(shape: Shape, topk_idx, place, alpha_num: int, alpha_den: int, ranks_per_node: int, load, input_eg,
+                    x_eg, comp_comm, pair_dst, row_of_pair, pair_of_row, seg_off, rank_off, ws):
+    cs = shape.c()
+    rc = load_library().fine_sched_comm(ctypes.byref(cs), _ptr(topk_idx), _ptr(place), alpha_num, alpha_den,
+                                        ranks_per_node, _ptr(load), _ptr(input_eg), _ptr(x_eg), _ptr(comp_comm),
+                                        _ptr(pair_dst), _ptr(row_of_pair), _ptr(pair_of_row), _ptr(seg_off),
+                                        _ptr(rank_off), _ptr(ws), ws.numel(), _stream())
+    _check("fine_sched_comm", rc)
+
+
+def fine_comm_replica_loads_host(load, input_eg, place, alpha_num: int, alpha_den: int):
+    """Host arrays in (anything numpy converts), (x_eg[E,G] int32, (C*, M*)) out; marshalling only."""
+    import numpy as np
+    load = np.ascontiguousarray(load, dtype=np.int32)
+    input_eg = np.ascontiguousarray(input_eg, dtype=np.int32)
+    place = np.ascontiguousarray(place, dtype=np.uint8)
+    E, G = place.shape
+    x = np.zeros((E, G), dtype=np.int32)
+    cc = np.zeros(2, dtype=np.int32)
+    rc = load_library().fine_comm_replica_loads_host(E, G, load.ctypes.data, input_eg.ctypes.data, place.ctypes.data,
+                                                     alpha_num, alpha_den, x.ctypes.data, cc.ctypes.data)
+    _check("fine_comm_replica_loads_host", rc)
+    return x, (int(cc[0]), int(cc[1]))
+
+
 def fine_permute(shape: Shape, x, pair_of_row, x_perm):
     cs = shape.c()
     _check("fine_permute", load_library().fine_permute(ctypes.byref(cs), _ptr(x), _ptr(pair_of_row), _ptr(x_perm), _stream()))
@@ -211,6 +242,19 @@ def fine_backward(shape: Shape, rank: int, d_out, x_perm, y_perm, act_save, w_ga
                                       _ptr(seg_off), _ptr(topk_w), _ptr(d_x), _ptr(d_topk_w), _ptr(d_w_gate),
                                       _ptr(d_w_up), _ptr(d_w_down), 1 if accumulate else 0, _ptr(ws), ws.numel(), _stream())
     _check("fine_backward", rc)
+
+
+def fine_cayley_placement(shape: Shape, orders, gens, complete: int, place):
+    """orders: sequence of ints; gens: sequence of tuples of len(orders) ints (host data); place: device tensor."""
+    k = len(orders)
+    o = (ctypes.c_int32 * k)(*[int(v) for v in orders])
+    flat = [int(v) for s in gens for v in s]
+    assert len(flat) == k * len(gens)
+    g = (ctypes.c_int32 * max(1, len(flat)))(*flat)
+    cs = shape.c()
+    rc = load_library().fine_cayley_placement(ctypes.byref(cs), k, ctypes.cast(o, ctypes.c_void_p), len(gens),
+                                              ctypes.cast(g, ctypes.c_void_p), complete, _ptr(place), _stream())
+    _check("fine_cayley_placement", rc)
 
 
 def fine_replica_counts(shape: Shape, load, slots: int, counts):

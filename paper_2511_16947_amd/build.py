@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libfinemoe.so")
-SOURCES = ["api.hip", "sched.hip", "general_x.hip", "topk.hip", "movement.hip", "ffn_simple.hip",
+SOURCES = ["api.hip", "sched.hip", "comm_sched.hip", "general_x.hip", "topk.hip", "movement.hip", "ffn_simple.hip",
            "ffn_mfma.hip", "backward.hip", "placement.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -102,6 +102,45 @@ int fine_sched(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* 
                            pair_of_row, seg_off, rank_off, ws, ws_bytes, stream);
 }
 
+int fine_sched_comm(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
+                    int32_t alpha_num, int32_t alpha_den, int32_t ranks_per_node,
+                    int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* comp_comm,
+                    int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
+                    int32_t* seg_off, int32_t* rank_off, void* ws, size_t ws_bytes, void* stream) {
+    FINE_TRY(check_shape(shape));
+    if (!topk_idx || !load || !input_eg || !x_eg || !comp_comm || !pair_dst || !row_of_pair || !pair_of_row ||
+        !seg_off || !rank_off || !ws)
+        return FINE_INVALID_ARG;
+    if (!aligned256(ws)) return FINE_INVALID_ARG;
+    if (alpha_num < 0 || alpha_den < 1 || ranks_per_node < 0 || shape->T == 0) return FINE_INVALID_ARG;
+    // the objective b C + a M is formed in 64 bits: P (a + b) must stay far below 2^63
+    if ((long long)alpha_num + alpha_den > (1ll << 30)) return FINE_INVALID_ARG;
+    if (ws_bytes < sched_ws_layout(*shape).total) return FINE_WORKSPACE_TOO_SMALL;
+    return launch_sched_comm(*shape, topk_idx, place, alpha_num, alpha_den, ranks_per_node, load, input_eg, x_eg, comp_comm,
+                             pair_dst, row_of_pair, pair_of_row, seg_off, rank_off, (char*)ws, (hipStream_t)stream);
+}
+
+int fine_comm_replica_loads_host(int32_t E, int32_t G, const int32_t* load_host, const int32_t* input_eg_host,
+                                 const uint8_t* place_host, int32_t alpha_num, int32_t alpha_den,
+                                 int32_t* x_eg_host, int32_t* comp_comm_host) {
+    if (!load_host || !input_eg_host || !place_host || !x_eg_host || !comp_comm_host) return FINE_INVALID_ARG;
+    if (E < 1 || G < 1 || alpha_num < 0 || alpha_den < 1 || (long long)alpha_num + alpha_den > (1ll << 30)) return FINE_INVALID_ARG;
+    if (E > 1024 || G > 64) return FINE_UNSUPPORTED;
+    long long P = 0;
+    for (int e = 0; e < E; ++e) {
+        long long row = 0;
+        for (int g = 0; g < G; ++g) {
+            if (input_eg_host[(size_t)e * G + g] < 0) return FINE_INVALID_ARG;
+            row += input_eg_host[(size_t)e * G + g];
+        }
+        if (row != load_host[e]) return FINE_INVALID_ARG;      // Table 1: sum_g input_e^g = load_e
+        P += row;
+    }
+    if (P >= (1ll << 31)) return FINE_UNSUPPORTED;
+    return comm_replica_loads_host(E, G, load_host, input_eg_host, place_host, alpha_num, alpha_den, x_eg_host,
+                                   comp_comm_host);
+}
+
 int fine_sched_static(const fine_shape* shape, const int32_t* topk_idx, const uint8_t* place,
                       int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
                       int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
@@ -173,6 +212,16 @@ int fine_backward(const fine_shape* shape, int32_t rank, const void* d_out,
     return launch_backward(*shape, lo, hi, d_out, x_perm, y_perm, act_save, w_gate, w_up, w_down, row_of_pair, pair_of_row,
                            seg_off, topk_w, d_x, d_topk_w, d_w_gate, d_w_up, d_w_down, accumulate, (char*)ws,
                            (hipStream_t)stream);
+}
+
+int fine_cayley_placement(const fine_shape* shape, int32_t n_factors, const int32_t* orders_host, int32_t n_gens,
+                          const int32_t* gens_host, int32_t complete, uint8_t* place, void* stream) {
+    FINE_TRY(check_shape(shape));
+    if (!orders_host || !place || (n_gens > 0 && !gens_host)) return FINE_INVALID_ARG;
+    if (n_factors < 1 || n_factors > kCayleyMaxFactors || n_gens < 0 || n_gens > kCayleyMaxGens || complete < 0 ||
+        complete > 1024)
+        return FINE_INVALID_ARG;
+    return launch_cayley_placement(*shape, n_factors, orders_host, n_gens, gens_host, complete, place, (hipStream_t)stream);
 }
 
 int fine_replica_counts(const fine_shape* shape, const int32_t* load, int32_t slots, int32_t* counts, void* stream) {

@@ -147,6 +147,19 @@ int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* pl
 constexpr size_t kSchedStaticBytes = (size_t)4 << 20;
 int sched_static_scratch(char** ptr);
 
+// parts of the scheduler, for entry points that compute the replica loads themselves
+int launch_sched_tables(const fine_shape& s, const int32_t* topk_idx, int32_t* load, int32_t* input_eg, char* ws,
+                        hipStream_t st);
+int launch_sched_routing(const fine_shape& s, const int32_t* topk_idx, int ranks_per_node, const int32_t* load,
+                         const int32_t* input_eg, int32_t* x_eg, int32_t* pair_dst, int32_t* row_of_pair,
+                         int32_t* pair_of_row, int32_t* seg_off, int32_t* rank_off, char* ws, hipStream_t st);
+int comm_replica_loads_host(int E, int G, const int32_t* load, const int32_t* input, const uint8_t* place, int alpha_num,
+                            int alpha_den, int32_t* x, int32_t* comp_comm);
+int launch_sched_comm(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place, int alpha_num, int alpha_den,
+                      int ranks_per_node, int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* comp_comm,
+                      int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row, int32_t* seg_off,
+                      int32_t* rank_off, char* ws, hipStream_t st);
+
 int launch_permute(const fine_shape& s, const void* x, const int32_t* pair_of_row, void* x_perm, hipStream_t st);
 int launch_combine(const fine_shape& s, const void* y_perm, const int32_t* row_of_pair,
                    const float* topk_w, void* out, hipStream_t st);
@@ -178,6 +191,9 @@ int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d
                     float* d_wd, int accumulate, char* ws, hipStream_t st);
 
 
+constexpr int kCayleyMaxFactors = 6, kCayleyMaxGens = 64;
+int launch_cayley_placement(const fine_shape& s, int n_factors, const int32_t* orders, int n_gens, const int32_t* gens,
+                            int complete, uint8_t* place, hipStream_t st);
 int launch_replica_counts(const fine_shape& s, const int32_t* load, int slots, int32_t* counts, hipStream_t st);
 int launch_eval_placements(const fine_shape& s, int n, const uint8_t* place, const int32_t* load, int64_t* m_num,
                            int32_t* m_den, hipStream_t st);

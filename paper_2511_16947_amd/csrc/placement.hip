@@ -447,6 +447,85 @@ size_t score_lds(int E, int G) { return ((size_t)(1 << (G < kLowMax ? G : kLowMa
 
 }  // namespace
 
+// ---- symmetric placements from Cayley graphs (Appendix B): expert = edge {a, a + s} ----------------
+struct CayleyDesc {
+    int n_factors, n_gens, complete;
+    int orders[kCayleyMaxFactors];
+    int gen[kCayleyMaxGens][kCayleyMaxFactors];      // reduced modulo the orders
+    int own_inverse[kCayleyMaxGens];
+    int first[kCayleyMaxGens + 1];                    // first expert of each generator's edges
+};
+
+namespace {
+
+__global__ __launch_bounds__(256) void k_cayley(CayleyDesc c, int E, int G, uint8_t* __restrict__ place) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= E * G) return;
+    const int e = i / G, g = i - e * G;
+    int a = 0, b = 0;
+    const int pairs = G * (G - 1) / 2;
+    if (e < c.complete * pairs) {
+        // pair number t of the pairs a < b in lexicographic order
+        int t = e % pairs;
+        a = 0;
+        while (t >= G - 1 - a) { t -= G - 1 - a; ++a; }
+        b = a + 1 + t;
+    } else {
+        int j = 0;
+        while (j + 1 < c.n_gens && e >= c.first[j + 1]) ++j;
+        int t = e - c.first[j];
+        // the t-th rank (ascending) that owns an edge of generator j
+        for (a = 0; a < G; ++a) {
+            int rest = a, w = 0, mul = 1;
+            for (int f = c.n_factors - 1; f >= 0; --f) {           // last factor fastest
+                const int n = c.orders[f], v = rest % n;
+                rest /= n;
+                w += ((v + c.gen[j][f]) % n) * mul;
+                mul *= n;
+            }
+            b = w;
+            if (c.own_inverse[j] && b < a) continue;
+            if (t-- == 0) break;
+        }
+    }
+    place[i] = (g == a || g == b) ? 1 : 0;
+}
+
+}  // namespace
+
+int launch_cayley_placement(const fine_shape& s, int n_factors, const int32_t* orders, int n_gens, const int32_t* gens,
+                            int complete, uint8_t* place, hipStream_t st) {
+    CayleyDesc c{};
+    c.n_factors = n_factors; c.n_gens = n_gens; c.complete = complete;
+    long long G = 1;
+    for (int f = 0; f < n_factors; ++f) {
+        if (orders[f] < 1) return FINE_INVALID_ARG;
+        c.orders[f] = orders[f];
+        G *= orders[f];
+        if (G > 64) return FINE_INVALID_ARG;
+    }
+    if (G != s.G) return FINE_INVALID_ARG;
+    long long count = (long long)complete * s.G * (s.G - 1) / 2;
+    for (int j = 0; j < n_gens; ++j) {
+        bool zero = true, own = true;
+        for (int f = 0; f < n_factors; ++f) {
+            const int n = orders[f], v = ((gens[j * n_factors + f] % n) + n) % n;
+            c.gen[j][f] = v;
+            zero = zero && v == 0;
+            own = own && (2 * v) % n == 0;
+        }
+        if (zero) return FINE_INVALID_ARG;                 // the identity is no generator
+        c.own_inverse[j] = own;
+        c.first[j] = (int)count;
+        count += own ? s.G / 2 : s.G;
+    }
+    c.first[n_gens] = (int)count;
+    if (count != s.E) return FINE_INVALID_ARG;
+    hipLaunchKernelGGL(k_cayley, dim3(cdiv(s.E * s.G, 256)), dim3(256), 0, st, c, s.E, s.G, place);
+    FINE_LAUNCH_CHECK();
+    return FINE_OK;
+}
+
 int launch_replica_counts(const fine_shape& s, const int32_t* load, int slots, int32_t* counts, hipStream_t st) {
     hipLaunchKernelGGL(k_replica_counts, dim3(1), dim3(64), 0, st, load, s.E, s.G, slots, counts);
     FINE_LAUNCH_CHECK();

@@ -97,10 +97,11 @@ __device__ inline int overlap(int a0, int alen, int b0, int blen) {
 // ---------------------------------------------------------------------------
 template <bool FULL>
 __global__ __launch_bounds__(64) void k_tables(const int32_t* __restrict__ load, const int32_t* __restrict__ input_eg,
-                                               int E, int G, int P, int locality,
+                                               int E, int G, int P, int locality, int rpn,
                                                int32_t* __restrict__ x_eg, int32_t* __restrict__ max_load,
                                                int32_t* __restrict__ Y, int32_t* __restrict__ Ypre) {
     __shared__ int s_loc[kWave], s_ri[kWave], s_rx[kWave], s_RI[kWave], s_RX[kWave];
+    __shared__ int s_nri[kWave], s_nrx[kWave], s_nI[kWave], s_nX[kWave];
     const int e = blockIdx.x, lane = lane_id();
     int xg = 0;
     if (FULL) {
@@ -119,8 +120,26 @@ __global__ __launch_bounds__(64) void k_tables(const int32_t* __restrict__ load,
     int in_g = (lane < G) ? input_eg[(size_t)e * G + lane] : 0;
     int loc = locality ? min(in_g, xg) : 0;
     int ri = in_g - loc, rx = xg - loc;
-    int RI = wave_incl_scan(ri) - ri, RX = wave_incl_scan(rx) - rx;
-    s_loc[lane] = loc; s_ri[lane] = ri; s_rx[lane] = rx; s_RI[lane] = RI; s_RX[lane] = RX;
+    // Pass inside the nodes (Appendix A.1's routing order: same GPU, same node, then any GPU; rpn
+    // consecutive ranks form a node, rpn <= 1: no such pass).  Inside a node the sources' waiting
+    // tokens and the replicas' free loads are two queues paired head to head, so source g meets
+    // replica h on the overlap of their intervals of the node's prefix sums, and what a rank has
+    // left afterwards is what lies beyond the other queue's end.
+    const bool nodes = rpn > 1;
+    int nI = 0, nX = 0, tI = 0, tX = 0;      // prefix inside the node, totals of the node
+    if (nodes) {
+        const int first = (lane / rpn) * rpn, last = min(first + rpn, kWave) - 1;
+        const int sI = wave_incl_scan(ri), sX = wave_incl_scan(rx);
+        const int bI = __shfl(sI, first, kWave) - __shfl(ri, first, kWave);
+        const int bX = __shfl(sX, first, kWave) - __shfl(rx, first, kWave);
+        nI = sI - ri - bI; nX = sX - rx - bX;
+        tI = __shfl(sI, last, kWave) - bI; tX = __shfl(sX, last, kWave) - bX;
+    }
+    const int ri2 = nodes ? ri - overlap(nI, ri, 0, tX) : ri;      // left for the pass over all ranks
+    const int rx2 = nodes ? rx - overlap(nX, rx, 0, tI) : rx;
+    int RI = wave_incl_scan(ri2) - ri2, RX = wave_incl_scan(rx2) - rx2;
+    s_loc[lane] = loc; s_ri[lane] = ri2; s_rx[lane] = rx2; s_RI[lane] = RI; s_RX[lane] = RX;
+    s_nri[lane] = ri; s_nrx[lane] = rx; s_nI[lane] = nI; s_nX[lane] = nX;
     __syncthreads();
     int32_t* Ye = Y + (size_t)e * G * G;
     int32_t* Yp = Ypre + (size_t)e * G * G;
@@ -129,6 +148,7 @@ __global__ __launch_bounds__(64) void k_tables(const int32_t* __restrict__ load,
         int run = 0;
         for (int g = 0; g < G; ++g) {
             int y = overlap(s_RI[g], s_ri[g], s_RX[h], s_rx[h]) + (g == h ? s_loc[g] : 0);
+            if (nodes && g / rpn == h / rpn) y += overlap(s_nI[g], s_nri[g], s_nX[h], s_nrx[h]);
             Ye[g * G + h] = y;
             Yp[g * G + h] = run;
             run += y;
@@ -182,7 +202,7 @@ __global__ __launch_bounds__(256) void k_segoff(const int32_t* __restrict__ x_eg
 // 5. One thread per pair: destination rank and row.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_pairs(const int32_t* __restrict__ topk_idx, int T, int K, int E, int G, int W,
-                                               int locality, const unsigned long long* __restrict__ bitmap,
+                                               int locality, int rpn, const unsigned long long* __restrict__ bitmap,
                                                const int32_t* __restrict__ cum, const int32_t* __restrict__ inpre,
                                                const int32_t* __restrict__ Y, const int32_t* __restrict__ Ypre,
                                                const int32_t* __restrict__ seg_off,
@@ -201,18 +221,23 @@ __global__ __launch_bounds__(256) void k_pairs(const int32_t* __restrict__ topk_
     int r = cum[(size_t)e * (W + 1) + w] + __popcll(bitmap[(size_t)e * W + w] & ((1ull << (t & 63)) - 1ull))
             - inpre[(size_t)e * G + g];           // rank of this token among (expert e, source g)
     const int32_t* Yrow = Y + ((size_t)e * G + g) * G;
+    // the hand-outs of source g in the order they were made: its own rank (locality), the ranks
+    // of its node in ascending order (rpn > 1), then the other ranks in ascending order
     int dst = -1, within = 0;
     if (locality) {
         int c = Yrow[g];
         if (r < c) { dst = g; within = r; } else r -= c;
     }
-    if (dst < 0) {
-        for (int h = 0; h < G; ++h) {
-            if (locality && h == g) continue;
-            int c = Yrow[h];
-            if (r < c) { dst = h; within = r; break; }
-            r -= c;
-        }
+    const int n0 = rpn > 1 ? (g / rpn) * rpn : 0, n1 = rpn > 1 ? min(n0 + rpn, G) : 0;      // the node of g
+    for (int h = n0; h < n1 && dst < 0; ++h) {
+        if (locality && h == g) continue;
+        int c = Yrow[h];
+        if (r < c) { dst = h; within = r; } else r -= c;
+    }
+    for (int h = 0; h < G && dst < 0; ++h) {
+        if ((locality && h == g) || (h >= n0 && h < n1)) continue;
+        int c = Yrow[h];
+        if (r < c) { dst = h; within = r; } else r -= c;
     }
     if (dst < 0) { pair_dst[p] = -1; row_of_pair[p] = p; pair_of_row[p] = p; return; }   // no schedule exists
     const int row = seg_off[(size_t)dst * (E + 1) + e] + Ypre[((size_t)e * G + g) * G + dst] + within;
@@ -239,42 +264,79 @@ SchedWs sched_ws_layout(const fine_shape& s) {
 int launch_general_x(const fine_shape& s, const uint8_t* place, const int32_t* load, const int32_t* x_prev,
                      int32_t* x_eg, int32_t* max_load, hipStream_t st);
 
+namespace {
+
+struct SchedArrays {
+    unsigned long long* bitmap;
+    int32_t *cum, *inpre, *Y, *Ypre;
+    int W;
+};
+SchedArrays sched_arrays(const fine_shape& s, char* ws) {
+    const SchedWs L = sched_ws_layout(s);
+    return {reinterpret_cast<unsigned long long*>(ws + L.bitmap), reinterpret_cast<int32_t*>(ws + L.cum),
+            reinterpret_cast<int32_t*>(ws + L.inpre), reinterpret_cast<int32_t*>(ws + L.Y),
+            reinterpret_cast<int32_t*>(ws + L.Ypre), L.W};
+}
+
+// segment offsets and per-pair indices from the routing tables in the workspace
+int launch_sched_indices(const fine_shape& s, const int32_t* topk_idx, int rpn, const int32_t* x_eg, const SchedArrays& a,
+                         int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row, int32_t* seg_off,
+                         int32_t* rank_off, hipStream_t st) {
+    const int P = s.T * s.K;
+    const int locality = (s.flags & FINE_FLAG_LOCALITY) ? 1 : 0;
+    hipLaunchKernelGGL(k_segoff, dim3(s.G), dim3(256), 0, st, x_eg, s.E, s.G, seg_off, rank_off);
+    FINE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_pairs, dim3(cdiv(P, 256)), dim3(256), 0, st,
+                       topk_idx, s.T, s.K, s.E, s.G, a.W, locality, rpn, a.bitmap, a.cum, a.inpre, a.Y, a.Ypre, seg_off,
+                       pair_dst, row_of_pair, pair_of_row);
+    FINE_LAUNCH_CHECK();
+    return FINE_OK;
+}
+
+}  // namespace
+
+// load tables (Table 1) into load / input_eg, token bitmaps and prefix counts into the workspace
+int launch_sched_tables(const fine_shape& s, const int32_t* topk_idx, int32_t* load, int32_t* input_eg, char* ws,
+                        hipStream_t st) {
+    const SchedArrays a = sched_arrays(s, ws);
+    hipLaunchKernelGGL(k_words, dim3(cdiv(a.W, 4)), dim3(256), (size_t)4 * s.E * 8, st,
+                       topk_idx, s.T, s.K, s.E, a.W, a.bitmap);
+    FINE_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_scan, dim3(s.E), dim3(64), (size_t)(a.W + 1) * 4, st,
+                       a.bitmap, s.T, s.G, a.W, a.cum, a.inpre, load, input_eg);
+    FINE_LAUNCH_CHECK();
+    return FINE_OK;
+}
+
+// Algorithm 1 (with the node pass when ranks_per_node > 1) and the indices, from given replica loads
+int launch_sched_routing(const fine_shape& s, const int32_t* topk_idx, int ranks_per_node, const int32_t* load,
+                         const int32_t* input_eg, int32_t* x_eg, int32_t* pair_dst, int32_t* row_of_pair,
+                         int32_t* pair_of_row, int32_t* seg_off, int32_t* rank_off, char* ws, hipStream_t st) {
+    const SchedArrays a = sched_arrays(s, ws);
+    const int locality = (s.flags & FINE_FLAG_LOCALITY) ? 1 : 0;
+    hipLaunchKernelGGL(k_tables<false>, dim3(s.E), dim3(64), 0, st,
+                       load, input_eg, s.E, s.G, s.T * s.K, locality, ranks_per_node, x_eg, (int32_t*)nullptr, a.Y, a.Ypre);
+    FINE_LAUNCH_CHECK();
+    return launch_sched_indices(s, topk_idx, ranks_per_node, x_eg, a, pair_dst, row_of_pair, pair_of_row, seg_off,
+                                rank_off, st);
+}
+
 int launch_sched(const fine_shape& s, const int32_t* topk_idx, const uint8_t* place, const int32_t* x_prev,
                  int32_t* load, int32_t* input_eg, int32_t* x_eg, int32_t* max_load,
                  int32_t* pair_dst, int32_t* row_of_pair, int32_t* pair_of_row,
                  int32_t* seg_off, int32_t* rank_off, char* ws, hipStream_t st) {
-    const SchedWs L = sched_ws_layout(s);
-    auto* bitmap = reinterpret_cast<unsigned long long*>(ws + L.bitmap);
-    auto* cum = reinterpret_cast<int32_t*>(ws + L.cum);
-    auto* inpre = reinterpret_cast<int32_t*>(ws + L.inpre);
-    auto* Y = reinterpret_cast<int32_t*>(ws + L.Y);
-    auto* Ypre = reinterpret_cast<int32_t*>(ws + L.Ypre);
-    const int P = s.T * s.K;
-    const int locality = (s.flags & FINE_FLAG_LOCALITY) ? 1 : 0;
-
-    hipLaunchKernelGGL(k_words, dim3(cdiv(L.W, 4)), dim3(256), (size_t)4 * s.E * 8, st,
-                       topk_idx, s.T, s.K, s.E, L.W, bitmap);
-    FINE_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_scan, dim3(s.E), dim3(64), (size_t)(L.W + 1) * 4, st,
-                       bitmap, s.T, s.G, L.W, cum, inpre, load, input_eg);
-    FINE_LAUNCH_CHECK();
-    if (place == nullptr) {
-        hipLaunchKernelGGL(k_tables<true>, dim3(s.E), dim3(64), 0, st,
-                           load, input_eg, s.E, s.G, P, locality, x_eg, max_load, Y, Ypre);
-        FINE_LAUNCH_CHECK();
-    } else {
+    FINE_TRY(launch_sched_tables(s, topk_idx, load, input_eg, ws, st));
+    if (place != nullptr) {
         FINE_TRY(launch_general_x(s, place, load, x_prev, x_eg, max_load, st));
-        hipLaunchKernelGGL(k_tables<false>, dim3(s.E), dim3(64), 0, st,
-                           load, input_eg, s.E, s.G, P, locality, x_eg, max_load, Y, Ypre);
-        FINE_LAUNCH_CHECK();
+        return launch_sched_routing(s, topk_idx, 0, load, input_eg, x_eg, pair_dst, row_of_pair, pair_of_row, seg_off,
+                                    rank_off, ws, st);
     }
-    hipLaunchKernelGGL(k_segoff, dim3(s.G), dim3(256), 0, st, x_eg, s.E, s.G, seg_off, rank_off);
+    const SchedArrays a = sched_arrays(s, ws);
+    const int locality = (s.flags & FINE_FLAG_LOCALITY) ? 1 : 0;
+    hipLaunchKernelGGL(k_tables<true>, dim3(s.E), dim3(64), 0, st,
+                       load, input_eg, s.E, s.G, s.T * s.K, locality, 0, x_eg, max_load, a.Y, a.Ypre);
     FINE_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_pairs, dim3(cdiv(P, 256)), dim3(256), 0, st,
-                       topk_idx, s.T, s.K, s.E, s.G, L.W, locality, bitmap, cum, inpre, Y, Ypre, seg_off,
-                       pair_dst, row_of_pair, pair_of_row);
-    FINE_LAUNCH_CHECK();
-    return FINE_OK;
+    return launch_sched_indices(s, topk_idx, 0, x_eg, a, pair_dst, row_of_pair, pair_of_row, seg_off, rank_off, st);
 }
 
 // ---------------------------------------------------------------------------

@@ -278,3 +278,28 @@ def test_layer_under_a_placement_built_from_its_own_loads():
     assert rows.max() == -(-P // G) == int(layer.sb.max_load.cpu()[0])      # complete balance (Section 6.3)
     ref = moe.dense_reference_by_expert(to64(inp.x), idx, to64(layer.topk_w), weights_of_factory(inp))
     assert max_rel_err(to64(layer.out), ref) <= 2e-2
+
+
+CAYLEY = [((8,), [(1,)], 0), ((4, 4), [(0, 1), (1, 0)], 0), ((2, 4), [(0, 1), (1, 1)], 0), ((2, 2, 2), [(0, 0, 1)], 1),
+          ((2, 2, 2, 2, 2), [(0, 0, 0, 0, 1), (0, 0, 0, 1, 0), (1, 1, 1, 1, 1)], 2), ((64,), [(1,), (5,), (32,), (-9,)], 0),
+          ((3, 5), [(1, 0), (0, 2), (2, 4)], 1), ((16,), [(s,) for s in range(1, 9)], 0)]
+
+
+@pytest.mark.parametrize("orders,gens,complete", CAYLEY, ids=[str(c[0]) + "+%d" % c[2] for c in CAYLEY])
+def test_cayley_placement_matches_the_oracle(orders, gens, complete):
+    """Appendix B's symmetric placements (Examples 1-4 and other groups, complete graphs first, generators
+    that are their own inverse): the device's masks equal the oracle's, expert by expert."""
+    want = placement.cayley_placement(orders, gens, complete)
+    E, G = want.shape
+    shape = fm.Shape(G, 64, 64, E, 1, G)
+    place = torch.full((E, G), 7, dtype=torch.uint8, device=DEV)
+    fm.fine_cayley_placement(shape, orders, gens, complete, place)
+    torch.cuda.synchronize()
+    assert np.array_equal(place.cpu().numpy(), want)
+    # a wrong number of experts, a generator that is the identity, orders that do not multiply to G
+    with pytest.raises(fm.FineError):
+        fm.fine_cayley_placement(fm.Shape(G, 64, 64, E + 1, 1, G), orders, gens, complete, torch.empty(E + 1, G, dtype=torch.uint8, device=DEV))
+    with pytest.raises(fm.FineError):
+        fm.fine_cayley_placement(shape, orders, [tuple(0 for _ in orders)] + list(gens[1:]), complete, place)
+    with pytest.raises(fm.FineError):
+        fm.fine_cayley_placement(shape, tuple(orders) + (2,), [tuple(g) + (0,) for g in gens], complete, place)

@@ -210,3 +210,60 @@ def test_density_by_flows_on_a_wide_placement_against_highs():
     assert abs(res.fun - float(m)) < 1e-6 * max(1.0, res.fun)
     assert m == Fraction(res.fun).limit_denominator(G)
     assert -(-m.numerator // m.denominator) == sched.min_max_load(load, place)
+
+
+# --------------------------------------------------------------------------
+# Cayley-graph placements (Appendix B)
+# --------------------------------------------------------------------------
+
+def edge_list(place):
+    out = []
+    for row in np.asarray(place):
+        ranks = np.nonzero(row)[0].tolist()
+        assert len(ranks) == 2
+        out.append(tuple(ranks))
+    return sorted(out)
+
+
+APPENDIX_B = [
+    ("example 1", dict(orders=(8,), gens=[(1,)], complete=0), wl.placement_cycle(8)),
+    ("example 2", dict(orders=(4, 4), gens=[(0, 1), (1, 0)], complete=0), wl.placement_torus4x4()),
+    ("example 3", dict(orders=(2, 4), gens=[(0, 1), (1, 1)], complete=0), wl.placement_z2xz4()),
+    ("example 4", dict(orders=(2, 2, 2), gens=[(0, 0, 1)], complete=1), wl.placement_complete_plus_matching(8)),
+]
+
+
+@pytest.mark.parametrize("name,args,want", APPENDIX_B, ids=[a[0] for a in APPENDIX_B])
+def test_cayley_generator_builds_the_examples_of_appendix_b(name, args, want):
+    """The generator against the four published constructions (whose edge lists are written out by
+    hand in workloads.py): the same edges, 2^p ranks with 2^q replicas each, 2^(p+q-1) experts."""
+    got = placement.cayley_placement(**args)
+    assert got.shape == want.shape
+    assert edge_list(got) == edge_list(want)
+    G = got.shape[1]
+    assert (got.sum(axis=0) == 2 * got.shape[0] // G).all()          # every rank holds the same number of replicas
+
+
+def test_cayley_example_3_is_the_complete_bipartite_graph():
+    """Appendix B: Example 3 is isomorphic to K_{4,4}; and for every size i the densest induced
+    subgraph on i ranks has as few edges as any 4-regular graph on 8 ranks allows."""
+    p = placement.cayley_placement((2, 4), [(0, 1), (1, 1)])
+    edges = edge_list(p)
+    other = {b for a, b in edges if a == 0} | {a for a, b in edges if b == 0}
+    mine = set(range(8)) - other
+    assert len(other) == 4 and len(mine) == 4
+    assert sorted(edges) == sorted((min(a, b), max(a, b)) for a in mine for b in other)
+    # densest induced subgraphs of K_{4,4}: i ranks hold at most floor(i/2) * ceil(i/2) edges
+    import itertools
+    for i in range(1, 9):
+        most = max(sum(1 for a, b in edges if a in S and b in S) for S in map(set, itertools.combinations(range(8), i)))
+        assert most == (i // 2) * ((i + 1) // 2)
+
+
+def test_cayley_generator_edge_cases():
+    with pytest.raises(ValueError):
+        placement.cayley_placement((4,), [(0,)])
+    # a generator that is its own inverse gives each edge once: Z_4 with {2} is two disjoint edges
+    assert edge_list(placement.cayley_placement((4,), [(2,)])) == [(0, 2), (1, 3)]
+    # generators are taken modulo the orders
+    assert edge_list(placement.cayley_placement((8,), [(-1,)])) == edge_list(placement.cayley_placement((8,), [(7,)]))
