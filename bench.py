@@ -303,13 +303,28 @@ def run_layer(args, cfg, dev, steps, warmup, cpu, restricted):
         dur_ms = sweep_ms(only1, it) - sweep_ms(none, it)            # the work-list kernel that precedes it is subtracted
         flops_per_launch = 4.0 * float(rank_rows.mean()) * s.d * s.f  # rows of the rank x (gate + up) x 2
         achieved = flops_per_launch / (dur_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "k_ffn_gemm_w8<EPI=0> (X[Wg|Wu]+SwiGLU), one launch per rank",
-                    "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
-                    "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name) if args.ffn == "per_rank" else None,
-                    "traffic_unit": "bytes leaving the L2s per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
-                                    "factors from the 1 GiB copy calibration; see profiles/)",
-                    "avg_launch_ms": round(dur_ms, 4), "flops_per_launch": flops_per_launch}
+        # algorithmic bytes of a launch: the rank's rows in, the gate and up weights of every expert it
+        # computes, H out.  Below the ridge (2500 TFLOP/s / 8 TB/s = 312 FLOP per byte) the launch is bound by
+        # streaming its weights from HBM and is priced against that roof.
+        experts_present = float((np.diff(sb.seg_off.cpu().numpy().astype(np.int64), axis=1) > 0).sum(axis=1).mean())
+        bytes_per_launch = (float(rank_rows.mean()) * (s.d + s.f) + experts_present * 2.0 * s.d * s.f) * 2.0
+        traffic_note = ("bytes leaving the L2s per launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, "
+                        "factors from the 1 GiB copy calibration; see profiles/)")
+        if flops_per_launch / bytes_per_launch < BF16_MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9):
+            gbs = bytes_per_launch / (dur_ms * 1e-3) / 1e9
+            roofline = {"bound": "hbm", "kernel": "k_ffn_gemm_w8<EPI=0> (X[Wg|Wu]+SwiGLU), one launch per rank",
+                        "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                        "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name) if args.ffn == "per_rank" else None,
+                        "traffic_unit": traffic_note, "avg_launch_ms": round(dur_ms, 4),
+                        "bytes_per_launch": bytes_per_launch, "experts_per_launch": round(experts_present, 2),
+                        "flops_per_launch": flops_per_launch, "TFLOPs": round(achieved, 2)}
+        else:
+            roofline = {"bound": "mfma", "kernel": "k_ffn_gemm_w8<EPI=0> (X[Wg|Wu]+SwiGLU), one launch per rank",
+                        "achieved": round(achieved, 2), "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(achieved / BF16_MFMA_PEAK_TFLOPS, 4),
+                        "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name) if args.ffn == "per_rank" else None,
+                        "traffic_unit": traffic_note,
+                        "avg_launch_ms": round(dur_ms, 4), "flops_per_launch": flops_per_launch}
     gemm1_roofline = roofline
     if do_bwd and wgrad_ms and not args.graph:
         # the dominant kernel of the training step: the three weight-gradient GEMMs of every expert in one

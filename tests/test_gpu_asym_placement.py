@@ -281,7 +281,7 @@ def test_layer_under_a_placement_built_from_its_own_loads():
 
 
 CAYLEY = [((8,), [(1,)], 0), ((4, 4), [(0, 1), (1, 0)], 0), ((2, 4), [(0, 1), (1, 1)], 0), ((2, 2, 2), [(0, 0, 1)], 1),
-          ((2, 2, 2, 2, 2), [(0, 0, 0, 0, 1), (0, 0, 0, 1, 0), (1, 1, 1, 1, 1)], 2), ((64,), [(1,), (5,), (32,), (-9,)], 0),
+          ((2, 2, 2, 2, 2), [(0, 0, 0, 0, 1), (0, 0, 0, 1, 0), (1, 1, 1, 1, 1)], 1), ((4, 2), [(1, 0), (2, 1)], 2), ((64,), [(1,), (5,), (32,), (-9,)], 0),
           ((3, 5), [(1, 0), (0, 2), (2, 4)], 1), ((16,), [(s,) for s in range(1, 9)], 0)]
 
 
