@@ -21,12 +21,17 @@ template <int WAVES_M, int WAVES_N, int WM, int WN>
 __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
                                             const uint16_t* __restrict__ act, int d, int f,
                                             uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
-                                            const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+                                            const TileEntry* __restrict__ tiles, int32_t* __restrict__ count) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int ntn = (f + BN - 1) / BN, ntm = *count, total = ntm * ntn;
-    for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
+    // tiles are handed out by UnitQueue (8 waves; its counters are zeroed by k_tile_map)
+    __shared__ int s_next;
+    const int bid = xcd_contiguous_id();
+    UnitQueue uq;
+    uq.init(count + kQueueOffset, kQueueStride, total, bid, W8);
+    for (int work = uq.first(bid); work >= 0; work = uq.next(work, &s_next)) {
         int tm, tn;
         tile_of_work(work, ntm, ntn, tm, tn);
         const TileEntry te = tiles[tm];
@@ -47,6 +52,7 @@ __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, con
             const int nf = min(4, max(0, (te.rows - (wave / WAVES_N) * WM * 32 + 31) / 32));
             if (te.rows == BM) k_loop8<false>(d / BK, smem, acc, oa, ob, k_tile);
             else k_loop8<true>(d / BK, smem, acc, oa, ob, k_tile, nf);
+            uq.request();      // the next tile, read after the epilogue
         } else {
             LoaderKC<BM> la;
             la.init([&](int r) { return dy + (size_t)(te.row0 + min(r, te.rows - 1)) * d; });
@@ -115,14 +121,14 @@ template <int WAVES_M, int WAVES_N, int WM, int WN>
 __global__ __launch_bounds__(256) void k_bwd_dh(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
                                                 const uint16_t* __restrict__ act, int d, int f,
                                                 uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
-                                                const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+                                                const TileEntry* __restrict__ tiles, int32_t* __restrict__ count) {
     bwd_dh_body<WAVES_M, WAVES_N, WM, WN>(dy, wd, act, d, f, dact, h, tiles, count);
 }
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 __global__ __launch_bounds__(512) void k_bwd_dh_w8(const uint16_t* __restrict__ dy, const uint16_t* __restrict__ wd,
                                                    const uint16_t* __restrict__ act, int d, int f,
                                                    uint16_t* __restrict__ dact, uint16_t* __restrict__ h,
-                                                   const TileEntry* __restrict__ tiles, const int32_t* __restrict__ count) {
+                                                   const TileEntry* __restrict__ tiles, int32_t* __restrict__ count) {
     bwd_dh_body<WAVES_M, WAVES_N, WM, WN>(dy, wd, act, d, f, dact, h, tiles, count);
 }
 
@@ -131,13 +137,17 @@ template <int WAVES_M, int WAVES_N, int WM, int WN>
 __device__ __forceinline__ void bwd_dx_body(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
                                             const uint16_t* __restrict__ wu, int d, int f,
                                             uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
-                                            const int32_t* __restrict__ count) {
+                                            int32_t* __restrict__ count) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int ntn = (d + BN - 1) / BN, ntm = *count, total = ntm * ntn;
     const int nkf = f / BK;
-    for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
+    __shared__ int s_next;
+    const int bid = xcd_contiguous_id();
+    UnitQueue uq;
+    uq.init(count + kQueueOffset + 8 * kQueueStride, kQueueStride, total, bid, W8);
+    for (int work = uq.first(bid); work >= 0; work = uq.next(work, &s_next)) {
         int tm, tn;
         tile_of_work(work, ntm, ntn, tm, tn);
         const TileEntry te = tiles[tm];
@@ -167,6 +177,7 @@ __device__ __forceinline__ void bwd_dx_body(const uint16_t* __restrict__ dact, c
             const int nf = min(4, max(0, (te.rows - (wave / WAVES_N) * WM * 32 + 31) / 32));
             if (te.rows == BM) k_loop8<false>(2 * nkf, smem, acc, oa, ob, k_tile);
             else k_loop8<true>(2 * nkf, smem, acc, oa, ob, k_tile, nf);
+            uq.request();
         } else {
             LoaderKC<BM> la;
             la.init([&](int r) { return dact + (size_t)(te.row0 + min(r, te.rows - 1)) * (2 * f); });
@@ -184,14 +195,14 @@ template <int WAVES_M, int WAVES_N, int WM, int WN>
 __global__ __launch_bounds__(256) void k_bwd_dx(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
                                                 const uint16_t* __restrict__ wu, int d, int f,
                                                 uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
-                                                const int32_t* __restrict__ count) {
+                                                int32_t* __restrict__ count) {
     bwd_dx_body<WAVES_M, WAVES_N, WM, WN>(dact, wg, wu, d, f, dxp, tiles, count);
 }
 template <int WAVES_M, int WAVES_N, int WM, int WN>
 __global__ __launch_bounds__(512) void k_bwd_dx_w8(const uint16_t* __restrict__ dact, const uint16_t* __restrict__ wg,
                                                    const uint16_t* __restrict__ wu, int d, int f,
                                                    uint16_t* __restrict__ dxp, const TileEntry* __restrict__ tiles,
-                                                   const int32_t* __restrict__ count) {
+                                                   int32_t* __restrict__ count) {
     bwd_dx_body<WAVES_M, WAVES_N, WM, WN>(dact, wg, wu, d, f, dxp, tiles, count);
 }
 
@@ -295,7 +306,7 @@ int run_dgrad(const fine_shape& s, int rank_lo, int rank_hi, const uint16_t* dy,
               const uint16_t* wd, const int32_t* seg_off, uint16_t* dact, uint16_t* h, uint16_t* dxp,
               TileEntry* tiles, int32_t* count, int max_tiles, bool run_dh, bool run_dx, hipStream_t st) {
     constexpr int BM = WAVES_M * WM * 32, BN = WAVES_N * WN * 32;
-    if (run_dh) FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));
+    FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, BM, tiles, count, max_tiles, st));      // also zeroes the queues
     const size_t lds = (size_t)2 * (BM + BN) * 128;
     constexpr bool W8 = WAVES_M * WAVES_N == 8;
     constexpr int threads = WAVES_M * WAVES_N * 64;

@@ -123,13 +123,13 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     };
 
     // Whole tiles first: as many full rounds of the grid as there are (4 waves: all tiles).
-    // 8 waves: the remaining rest < nblk tiles are rest * nk k-steps; block b takes steps
-    // [b * per, (b+1) * per) of that sequence.  A block that computes only part of a tile's k
-    // range writes its accumulators to its slot (two per block: a range begins and ends inside
+    // 8 waves: the remaining rest < nblk tiles are rest * nk k-steps, cut into nblk parts: part p is
+    // steps [p * per, (p+1) * per) of that sequence.  Whoever computes only part of a tile's k
+    // range writes its accumulators to the part's slot (two per part: a range begins and ends inside
     // at most one tile each) and counts itself in; whoever counts in last adds the parts up in
-    // block order - the same sum whoever it is - and runs the epilogue.  Nobody waits.  (A rest too
+    // part order - the same sum whoever it is - and runs the epilogue.  Nobody waits.  (A rest too
     // small for that to pay is cut into few parts instead, see below.)
-    __shared__ int s_last;
+    __shared__ int s_last, s_next;
     const int nblk = gridDim.x, bid = xcd_contiguous_id();
     // the cut pays when the k-steps it saves (the last round would take nk, the cut takes
     // rest * nk / nblk) outweigh writing, re-reading and adding up partial tiles.  Measured
@@ -141,7 +141,7 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     // Below that break-even a small rest would still cost a whole extra round (24 of 280 tiles of 32
     // steps: one more tile time with 232 CUs idle).  Spreading so few steps over the whole grid would
     // leave each tile in ten parts for its last block to add up; instead every rest tile is cut into 2
-    // or 4 parts of at least 8 steps, part p of rest tile t going to block t + p * rest ("few parts").
+    // or 4 parts of at least 8 steps, part t + p * rest being k range p of rest tile t ("few parts").
     const int rest_if = total - whole_rounds;
     int few = 0;
     if (W8 && !cut && rest_if > 0)
@@ -150,8 +150,9 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     const int full = (cut || few) ? whole_rounds : total;
     const int rest = total - full;
     const int per = (rest * nk + nblk - 1) / nblk;
+    const int nparts = cut ? nblk : rest * few;
     int32_t* counters = count + kSkCounterOffset;
-    auto slot_of = [&](int blk, int t) { return few ? blk * 2 : blk * 2 + (((blk * per) / nk) == t ? 0 : 1); };
+    auto slot_of = [&](int part, int t) { return few ? part * 2 : part * 2 + (((part * per) / nk) == t ? 0 : 1); };
     // Partial sums travel as 16-byte buffer stores and loads with the sc0 sc1 cache policy: they
     // are written through and read past the per-XCD L2 one by one, so no cache-wide write-back or
     // invalidate (a fence) is needed, which would cost every block on the XCD its cached operand
@@ -163,45 +164,33 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     constexpr int kCoherent = 1 | 16;      // sc0 | sc1
     const __amdgpu_buffer_rsrc_t sk_rs =
         __builtin_amdgcn_make_buffer_rsrc((void*)sk_partials, 0, (int)(2 * 256 * (size_t)kSlotBytes), 0x00020000);
-    int next_whole = bid, u = bid * per;
-    const int u1 = min(rest * nk, u + per);
-    bool part_taken = false;
-    for (;;) {
-        int work, kb = 0, kn = nk;
-        if (next_whole < full) {
-            work = next_whole;
-            next_whole += nblk;
-        } else if (W8 && few) {
-            if (part_taken || bid >= rest * few) break;
-            part_taken = true;
-            kn = nk / few;
-            kb = (bid / rest) * kn;
-            work = full + bid % rest;
-        } else if (W8 && u < u1) {
-            const int t = u / nk;
-            kb = u - t * nk;
-            kn = min(nk - kb, u1 - u);
-            work = full + t;
-            u += kn;
-        } else {
-            break;
-        }
+
+    // Who computes what: the units of a launch are its whole tiles [0, full) and then its parts
+    // [full, full + nparts); 8 waves: handed out by UnitQueue (counters zeroed by k_tile_map).
+    UnitQueue uq;
+    uq.init(count + kQueueOffset + (EPI * 8) * kQueueStride, kQueueStride, full + nparts, bid, W8);
+    auto request = [&]() { uq.request(); };
+
+    // k-tiles [kb, kb + kn) of tile `work`; part: the part this piece belongs to (-1: a whole tile);
+    // ask: request the next unit after the k-loop
+    auto piece = [&](int work, int kb, int kn, int part, bool ask) {
         zero_acc<WM, WN>(acc);
         run_tile(work, kb, kn);
+        if (ask) request();
         bool finish = true;
         if constexpr (W8) {
             if (kn != nk) {
                 const int t = work - full;
-                // the blocks that hold parts of tile t: first, first + step, ... (n_parts of them)
+                // the parts that hold pieces of tile t: first, first + step, ... (n_parts of them)
                 const int first = few ? t : (t * nk) / per;
                 const int step = few ? rest : 1;
                 const int n_parts = few ? few : (t * nk + nk - 1) / per - first + 1;
-                const int mine = slot_of(bid, t);
+                const int mine = slot_of(part, t);
                 static_for<WM * WN>([&](auto m) {
                     static_for<4>([&](auto q) {
                         const f32x16& v = acc[m.value / WN][m.value % WN];
-                        const f32x4 part = {v[4 * q.value], v[4 * q.value + 1], v[4 * q.value + 2], v[4 * q.value + 3]};
-                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, part), sk_rs, threadIdx.x * 16,
+                        const f32x4 val = {v[4 * q.value], v[4 * q.value + 1], v[4 * q.value + 2], v[4 * q.value + 3]};
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), sk_rs, threadIdx.x * 16,
                                                                mine * kSlotBytes + (m.value * 4 + q.value) * kThreadsBlk * 16,
                                                                kCoherent);
                     });
@@ -225,9 +214,9 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                             });
                             static_for<8>([&](auto g) {
                                 constexpr int m = mp.value * 2 + g.value / 4, q = g.value % 4;
-                                const f32x4 part = __builtin_bit_cast(f32x4, v[g.value]);
+                                const f32x4 val = __builtin_bit_cast(f32x4, v[g.value]);
                                 f32x16& a = acc[m / WN][m % WN];
-                                a[4 * q] += part[0]; a[4 * q + 1] += part[1]; a[4 * q + 2] += part[2]; a[4 * q + 3] += part[3];
+                                a[4 * q] += val[0]; a[4 * q + 1] += val[1]; a[4 * q + 2] += val[2]; a[4 * q + 3] += val[3];
                             });
                             __builtin_amdgcn_sched_barrier(0);      // keeps the loads from piling up in registers
                         });
@@ -238,6 +227,29 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
             }
         }
         if (finish) epilogue(work);
+    };
+
+    if constexpr (!W8) {
+        for (int work = bid; work < total; work += nblk) piece(work, 0, nk, -1, false);
+    } else {
+        for (int v = uq.first(bid); v >= 0; v = uq.next(v, &s_next)) {
+            if (v < full) {
+                piece(v, 0, nk, -1, true);
+            } else if (few) {
+                const int part = v - full, kn = nk / few;
+                piece(full + part % rest, (part / rest) * kn, kn, part, true);
+            } else {
+                const int part = v - full;
+                int u = part * per;
+                const int u1 = min(rest * nk, u + per);
+                if (u >= u1) request();      // (an empty part at the end of the sequence)
+                while (u < u1) {
+                    const int t = u / nk, kb = u - t * nk, kn = min(nk - kb, u1 - u);
+                    piece(full + t, kb, kn, part, u + kn >= u1);
+                    u += kn;
+                }
+            }
+        }
     }
 }
 

@@ -419,6 +419,80 @@ __device__ inline void tile_of_work(int work, int ntm, int ntn, int& tm, int& tn
     tm = b * h0 + min(b, extra) + rr % h;
 }
 
+// Handing out the units of a persistent launch (whole tiles, then parts of tiles) to its blocks.
+// The fixed order gives block b the units b, b + nblk, ...  With at most two rounds of units that
+// order is kept.  With more rounds the units differ in cost (a short last row tile of a segment
+// skips most of its MFMAs; a launch over all ranks mixes segments of all lengths), so from the
+// second round on they are handed out as blocks become free.  XCD x owns the units that the fixed
+// order would give its blocks (unit (j / per_x) * nblk + x * per_x + j % per_x for j = 0, 1, ...: 32
+// consecutive units, one patch of tile_of_work, per round) and its blocks take them in that order
+// from the XCD's queue counter (zero at launch; position = counter + per_x, the first round being
+// the fixed one).  A block that finds its XCD's queue empty reads the other seven counters once
+// and then takes from those that still have units.  The request for the next unit is sent before
+// a unit's epilogue and read after it, so that its latency is hidden.
+struct UnitQueue {
+    int32_t* queues;      // 8 counters, `stride` int32 apart
+    int stride, nunits, nblk, per_x, my_x, list_len;
+    bool queued;
+    // thread 0 only: queues (relative to the block's own) that may still have units, whether the
+    // other queues have been looked at, the queue asked last and what it returned
+    int open = 1, cur = 0, got = 0;
+    bool probed = false;
+
+    // bid: the block's place in the fixed order (xcd_contiguous_id())
+    __device__ inline void init(int32_t* queues_, int stride_, int nunits_, int bid, bool allowed) {
+        queues = queues_;
+        stride = stride_;
+        nunits = nunits_;
+        nblk = gridDim.x;
+        per_x = max(nblk / 8, 1);
+        my_x = bid / per_x;
+        list_len = ((nunits + nblk - 1) / nblk) * per_x;
+        queued = allowed && nblk % 8 == 0 && nunits > 2 * nblk;
+    }
+    __device__ inline int32_t* queue_of(int i) const { return queues + ((my_x + i) & 7) * stride; }
+    __device__ inline int first(int bid) const { return bid < nunits ? bid : -1; }
+    __device__ inline void request() {
+        if (queued && threadIdx.x == 0 && open != 0) {
+            cur = __builtin_ctz(open);
+            got = __hip_atomic_fetch_add(queue_of(cur), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    // all threads: the unit after v for this block, or -1 (s_next: one int of LDS; contains a block barrier
+    // when the launch is queued)
+    __device__ inline int next(int v, int* s_next) {
+        if (!queued) return v + nblk < nunits ? v + nblk : -1;
+        if (threadIdx.x == 0) {
+            int found = -1;
+            while (open != 0) {
+                const int j = got + per_x;
+                if (j < list_len) {
+                    const int cand = (j / per_x) * nblk + ((my_x + cur) & 7) * per_x + j % per_x;
+                    if (cand < nunits) { found = cand; break; }
+                    // (a position of the last round past the last unit: the same queue is asked again)
+                } else {
+                    open &= ~(1 << cur);
+                    if (!probed) {
+                        probed = true;
+                        int seen[8];
+                        for (int i = 1; i < 8; ++i)
+                            seen[i] = __hip_atomic_load(queue_of(i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        for (int i = 1; i < 8; ++i)
+                            if (seen[i] + per_x < list_len) open |= 1 << i;
+                    }
+                }
+                if (open != 0) {
+                    cur = __builtin_ctz(open);
+                    got = __hip_atomic_fetch_add(queue_of(cur), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            *s_next = found;
+        }
+        __syncthreads();
+        return __builtin_amdgcn_readfirstlane(*s_next);
+    }
+};
+
 constexpr int share_begin(int slot, int total, int slots) { return (total * slot) / slots; }
 
 

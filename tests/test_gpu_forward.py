@@ -225,6 +225,43 @@ def test_a_small_rest_of_tiles_is_cut_into_few_parts(tile, d, f, T, parts):
         assert torch.equal(layer.y_perm, first)
 
 
+def test_units_of_a_long_launch_are_handed_out_from_queues():
+    """More than two rounds of tiles in both GEMMs of one call (572 column-by-row tiles on 256 blocks,
+    the rest cut along k): from the second round on the blocks take their tiles from the per-XCD
+    queues, whoever is free first.  Every element and every row against the oracle, ragged row
+    tiles of several lengths among whole ones, the call for all ranks and the calls rank by rank,
+    and bit-stable from run to run (which block computes a tile must not matter)."""
+    cfg = wl.LayerConfig("queues", 2688, 5632, 2816, 8, 2, 2, "bf16", 13, "scaled_z", 1.0)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (3 << 8))
+    print("queue case", flush=True)
+    layer.y_perm.fill_(float("nan"))
+    layer.forward()
+    idx = layer.topk_idx.cpu().numpy()
+    want = check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G)
+    seg = np.diff(want["seg_off"], axis=1)
+    row_tiles = int((-(-seg // 256)).sum())
+    assert row_tiles * (cfg.f // 128) > 512 and row_tiles * (cfg.d // 256) > 512      # the case is what it says
+    assert ((seg % 256) != 0).sum() >= 4
+    weights_of = weights_of_factory(inp)
+    ref_y = moe.grouped_ffn(moe.permute(to64(inp.x), want["pair_of_row"], cfg.K), want["seg_off"], weights_of)
+    got = to64(layer.y_perm)
+    assert max_rel_err(got, ref_y) <= tol_for(cfg)
+    assert max_rel_err_rows(got, ref_y) <= tol_for(cfg)
+    first = layer.y_perm.clone()
+    for _ in range(3):
+        layer.y_perm.zero_()
+        layer.ffn(-1)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.y_perm, first)
+    # rank by rank the tiles that are cut along k are other ones: equal within rounding, not bit by bit
+    layer.y_perm.fill_(float("nan"))
+    for r in range(cfg.G):
+        layer.ffn(r)
+    torch.cuda.synchronize()
+    assert max_rel_err_rows(to64(layer.y_perm), ref_y) <= tol_for(cfg)
+
+
 def test_act_save_holds_the_preactivations():
     cfg = wl.scaled(wl.CONFIGS["cfg2_mixtral"], name="cfg2_small", T=512, d=128, f=256)
     inp = wl.make_inputs(cfg, DEV)
