@@ -226,6 +226,12 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
     const int t2 = cdiv_dev(p2.M, BM) * cdiv_dev(p2.N, BN);
     const int per_expert = t0 + t1 + t2;
     const int total = per_expert * E;
+    // The rows of an expert: its non-empty segments on the ranks [g_lo, g_hi), ascending, gathered
+    // into LDS when the block moves on to another expert (its tiles follow one another in the work
+    // list): s_seg[2 i], s_seg[2 i + 1] = first row and end of segment i; then their number and the
+    // number of 64-row k-tiles.  At most 64 ranks: one lane per rank.
+    __shared__ int s_seg[2 * 64 + 2];
+    int seg_expert = -1, nk = 0;
     for (int work = xcd_contiguous_id(); work < total; work += gridDim.x) {
         const int e = work / per_expert;
         int j = work - e * per_expert;
@@ -235,17 +241,41 @@ __device__ __forceinline__ void wgrad_body(WgradProblem p0, WgradProblem p1, Wgr
         int tm, tn;
         tile_of_work(j, cdiv_dev(p.M, BM), cdiv_dev(p.N, BN), tm, tn);
         const int m0 = tm * BM, n0 = tn * BN;
-        // k-tiles: 64 rows at a time through the expert's segment on every rank of [g_lo, g_hi), ascending
-        int nk = 0;
-        for (int g = g_lo; g < g_hi; ++g)
-            nk += (seg_off[(size_t)g * (E + 1) + e + 1] - seg_off[(size_t)g * (E + 1) + e] + BK - 1) / BK;
+        if (e != seg_expert) {                     // (block-uniform)
+            __syncthreads();                       // nobody still walks the previous expert's list
+            if (threadIdx.x < 64) {
+                const int g = g_lo + (int)threadIdx.x;
+                int lo = 0, hi = 0;
+                if (g < g_hi) {
+                    lo = seg_off[(size_t)g * (E + 1) + e];
+                    hi = seg_off[(size_t)g * (E + 1) + e + 1];
+                }
+                const bool has = hi > lo;
+                const unsigned long long m = __ballot(has);
+                const int pos = __popcll(m & ((1ull << threadIdx.x) - 1ull));
+                if (has) {
+                    s_seg[2 * pos] = lo;
+                    s_seg[2 * pos + 1] = hi;
+                }
+                int steps = has ? (hi - lo + BK - 1) / BK : 0;
+                for (int o = 32; o > 0; o >>= 1) steps += __shfl_xor(steps, o);
+                if (threadIdx.x == 0) {
+                    s_seg[128] = __popcll(m);
+                    s_seg[129] = steps;
+                }
+            }
+            __syncthreads();
+            seg_expert = e;
+            nk = __builtin_amdgcn_readfirstlane(s_seg[129]);
+        }
         if (nk == 0 && accumulate) continue;      // nothing to add (block-uniform)
-        int cur_g = g_lo - 1, cur_k = 0, cur_lo = 0, cur_hi = 0;
+        // k-tiles: 64 rows at a time through the segments in order
+        int cur_i = -1, cur_k = 0, cur_lo = 0, cur_hi = 0;
         auto k_tile = [&](int) {
-            while (cur_k >= cur_hi) {          // advance to the next non-empty segment
-                ++cur_g;
-                cur_lo = cur_k = seg_off[(size_t)cur_g * (E + 1) + e];
-                cur_hi = seg_off[(size_t)cur_g * (E + 1) + e + 1];
+            if (cur_k >= cur_hi) {             // on to the next segment
+                ++cur_i;
+                cur_lo = cur_k = __builtin_amdgcn_readfirstlane(s_seg[2 * cur_i]);
+                cur_hi = __builtin_amdgcn_readfirstlane(s_seg[2 * cur_i + 1]);
             }
             const KTile t{(ptrdiff_t)cur_k, (ptrdiff_t)cur_k, cur_hi, cur_lo};
             cur_k += BK;

@@ -428,7 +428,7 @@ __device__ inline void tile_of_work(int work, int ntm, int ntn, int& tm, int& tn
 // consecutive units, one patch of tile_of_work, per round) and its blocks take them in that order
 // from the XCD's queue counter (zero at launch; position = counter + per_x, the first round being
 // the fixed one).  A block that finds its XCD's queue empty reads the other seven counters once
-// and then takes from those that still have units.  The request for the next unit is sent before
+// and then takes from those that still have more than half a round of units.  The request for the next unit is sent before
 // a unit's epilogue and read after it, so that its latency is hidden.
 struct UnitQueue {
     int32_t* queues;      // 8 counters, `stride` int32 apart
@@ -477,8 +477,9 @@ struct UnitQueue {
                         int seen[8];
                         for (int i = 1; i < 8; ++i)
                             seen[i] = __hip_atomic_load(queue_of(i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        // (a queue about to run out is left to its own blocks)
                         for (int i = 1; i < 8; ++i)
-                            if (seen[i] + per_x < list_len) open |= 1 << i;
+                            if (seen[i] + per_x + per_x / 2 < list_len) open |= 1 << i;
                     }
                 }
                 if (open != 0) {
