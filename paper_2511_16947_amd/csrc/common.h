@@ -99,15 +99,16 @@ struct TileEntry {
     int32_t seg_rows;  // rows of the whole segment
 };
 
-// The count block: int32 number of row tiles, and from int32 index kSkCounterOffset on 256
-// arrival counters for tiles cut along k (zero between launches).  Partial sums of such tiles:
+// The count block: int32 number of row tiles, from int32 index kSkCounterOffset on 256 arrival
+// counters for tiles cut along k and from kSkReadyOffset on their 256 "parts written" counters
+// (all zero between launches).  Partial sums of such tiles:
 // two slots of one 256 x 256 fp32 tile for each of the 256 parts of a launch.
 // From int32 index kQueueOffset on: the work queues of the 8-wave GEMM launches that follow a
 // k_tile_map (which zeroes them) - queue q at kQueueOffset + q * kQueueStride, one cache line
 // each; a launch uses 8 of them (one per XCD), the second GEMM of a call the next 8.
-constexpr size_t kCountBytes = 4096;
-constexpr int kSkCounterOffset = 64;
-constexpr int kQueueOffset = 512, kQueueStride = 32, kQueues = 16;
+constexpr size_t kCountBytes = 8192;
+constexpr int kSkCounterOffset = 64, kSkReadyOffset = 320;
+constexpr int kQueueOffset = 1024, kQueueStride = 32, kQueues = 16;
 constexpr size_t kSkBytes = (size_t)512 * 256 * 256 * 4;
 
 struct FfnWs {

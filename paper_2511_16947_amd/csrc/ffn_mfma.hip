@@ -125,10 +125,13 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     // Whole tiles first: as many full rounds of the grid as there are (4 waves: all tiles).
     // 8 waves: the remaining rest < nblk tiles are rest * nk k-steps, cut into nblk parts: part p is
     // steps [p * per, (p+1) * per) of that sequence.  Whoever computes only part of a tile's k
-    // range writes its accumulators to the part's slot (two per part: a range begins and ends inside
-    // at most one tile each) and counts itself in; whoever counts in last adds the parts up in
-    // part order - the same sum whoever it is - and runs the epilogue.  Nobody waits.  (A rest too
-    // small for that to pay is cut into few parts instead, see below.)
+    // range counts itself in when its k-loop is done; all but the last to do so write their
+    // accumulators to their part's slot (two per part: a range begins and ends inside at most one
+    // tile each) and count themselves ready; the last keeps its accumulators, waits until the others
+    // are ready (they are past their k-loops and wait for nothing), adds the parts up in part order -
+    // the same sum whoever it is - and runs the epilogue.  Partial sums are traffic at the end of a
+    // launch, when every block has them at once: one write and one read per part that is not last.
+    // (A rest too small for the cut to pay is cut into few parts instead, see below.)
     __shared__ int s_last, s_next;
     const int nblk = gridDim.x, bid = xcd_contiguous_id();
     // the cut pays when the k-steps it saves (the last round would take nk, the cut takes
@@ -151,7 +154,8 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     const int rest = total - full;
     const int per = (rest * nk + nblk - 1) / nblk;
     const int nparts = cut ? nblk : rest * few;
-    int32_t* counters = count + kSkCounterOffset;
+    int32_t* counters = count + kSkCounterOffset;      // arrivals per rest tile
+    int32_t* ready = count + kSkReadyOffset;           // parts written per rest tile
     auto slot_of = [&](int part, int t) { return few ? part * 2 : part * 2 + (((part * per) / nk) == t ? 0 : 1); };
     // Partial sums travel as 16-byte buffer stores and loads with the sc0 sc1 cache policy: they
     // are written through and read past the per-XCD L2 one by one, so no cache-wide write-back or
@@ -185,26 +189,49 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                 const int first = few ? t : (t * nk) / per;
                 const int step = few ? rest : 1;
                 const int n_parts = few ? few : (t * nk + nk - 1) / per - first + 1;
-                const int mine = slot_of(part, t);
-                static_for<WM * WN>([&](auto m) {
-                    static_for<4>([&](auto q) {
-                        const f32x16& v = acc[m.value / WN][m.value % WN];
-                        const f32x4 val = {v[4 * q.value], v[4 * q.value + 1], v[4 * q.value + 2], v[4 * q.value + 3]};
-                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), sk_rs, threadIdx.x * 16,
-                                                               mine * kSlotBytes + (m.value * 4 + q.value) * kThreadsBlk * 16,
-                                                               kCoherent);
-                    });
-                });
-                __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0): this thread's partial sums have been written
-                __syncthreads();
+                // Whoever arrives last (everybody else has left its k-loop by then) adds the parts up; the
+                // others write theirs to their slots and then count themselves ready.  The tile is
+                // part 0 + part 1 + part 2 + ... in that order whoever adds: if the last one holds part 0 or
+                // part 1 it keeps it in its accumulators (x + y = y + x to the bit, so the chain may start
+                // from either of the two) and reads only the others; if it holds a later part it writes that
+                // one too and reads them all.
                 if (threadIdx.x == 0)
                     s_last = __hip_atomic_fetch_add(&counters[t], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                              n_parts - 1;
                 __syncthreads();
                 finish = s_last != 0;
+                const int my_idx = (part - first) / step;
+                const bool keep = finish && my_idx <= 1;
+                if (!keep) {
+                    const int mine = slot_of(part, t);
+                    static_for<WM * WN>([&](auto m) {
+                        static_for<4>([&](auto q) {
+                            const f32x16& v = acc[m.value / WN][m.value % WN];
+                            const f32x4 val = {v[4 * q.value], v[4 * q.value + 1], v[4 * q.value + 2], v[4 * q.value + 3]};
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, val), sk_rs, threadIdx.x * 16,
+                                                                   mine * kSlotBytes + (m.value * 4 + q.value) * kThreadsBlk * 16,
+                                                                   kCoherent);
+                        });
+                    });
+                    __builtin_amdgcn_s_waitcnt(0x0070);      // vmcnt(0): this thread's partial sums have been written
+                    __syncthreads();
+                    if (!finish && threadIdx.x == 0)
+                        __hip_atomic_fetch_add(&ready[t], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
                 if (finish) {
-                    zero_acc<WM, WN>(acc);
-                    for (int i = 0; i < n_parts; ++i) {
+                    // The others are past their k-loops and on their way through the lines above, which wait
+                    // for nothing but their own stores: this wait ends.  (The bound only keeps a mistake
+                    // elsewhere from hanging the launch: the sums would then be wrong, not the GPU stuck.)
+                    if (threadIdx.x == 0) {
+                        int polls = 0;
+                        while (__hip_atomic_load(&ready[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < n_parts - 1 &&
+                               ++polls < (1 << 20))
+                            __builtin_amdgcn_s_sleep(4);
+                        ready[t] = 0;          // both counters are zero again for the next launch
+                        counters[t] = 0;
+                    }
+                    __syncthreads();
+                    auto add_part = [&](int i, auto assign) {
                         const int sl = slot_of(first + i * step, t);
                         static_for<WM * WN / 2>([&](auto mp) {
                             u32x4 v[8];
@@ -216,12 +243,18 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                                 constexpr int m = mp.value * 2 + g.value / 4, q = g.value % 4;
                                 const f32x4 val = __builtin_bit_cast(f32x4, v[g.value]);
                                 f32x16& a = acc[m / WN][m % WN];
-                                a[4 * q] += val[0]; a[4 * q + 1] += val[1]; a[4 * q + 2] += val[2]; a[4 * q + 3] += val[3];
+                                if constexpr (assign.value) {
+                                    a[4 * q] = val[0]; a[4 * q + 1] = val[1]; a[4 * q + 2] = val[2]; a[4 * q + 3] = val[3];
+                                } else {
+                                    a[4 * q] += val[0]; a[4 * q + 1] += val[1]; a[4 * q + 2] += val[2]; a[4 * q + 3] += val[3];
+                                }
                             });
                             __builtin_amdgcn_sched_barrier(0);      // keeps the loads from piling up in registers
                         });
-                    }
-                    if (threadIdx.x == 0) counters[t] = 0;      // ready for the next launch
+                    };
+                    if (!keep) add_part(0, std::true_type{});
+                    for (int i = keep ? 0 : 1; i < n_parts; ++i)
+                        if (!(keep && i == my_idx)) add_part(i, std::false_type{});
                 }
                 __syncthreads();
             }

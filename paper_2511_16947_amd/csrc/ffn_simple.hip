@@ -16,6 +16,7 @@ __global__ __launch_bounds__(256) void k_tile_map(const int32_t* __restrict__ se
     const int tid = threadIdx.x;
     if (tid == 0) s_carry = 0;
     count[kSkCounterOffset + tid] = 0;
+    count[kSkReadyOffset + tid] = 0;
     if (tid < kQueues) count[kQueueOffset + tid * kQueueStride] = 0;
     __syncthreads();
     const int nseg = (rank_hi - rank_lo) * E;
