@@ -137,7 +137,10 @@ def run_layer(args, cfg, dev, steps, warmup, cpu, restricted):
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
-    shape = fm.shape_of(cfg, fm.FLAG_LOCALITY | (args.tile << 8))
+    do_bwd = cfg.backward and not args.no_backward
+    # training keeps the pre-activations A|B [P,2f] of the forward pass, and H [P,f] behind them, for the backward pass
+    keep_act = do_bwd and not args.recompute
+    shape = fm.shape_of(cfg, fm.FLAG_LOCALITY | (args.tile << 8) | (fm.FLAG_ACT_SAVE_H if keep_act else 0))
     s = shape
     topk_idx = torch.empty(s.T, s.K, dtype=torch.int32, device=dev)
     topk_w = torch.empty(s.T, s.K, dtype=torch.float32, device=dev)
@@ -147,7 +150,6 @@ def run_layer(args, cfg, dev, steps, warmup, cpu, restricted):
     out = torch.empty(s.T, s.d, dtype=s.torch_dtype, device=dev)
     ws_ffn = fm.alloc_workspace(s, fm.WS_FFN, dev)
     ws_topk = fm.alloc_workspace(s, fm.WS_TOPK, dev)
-    do_bwd = cfg.backward and not args.no_backward
     if do_bwd:
         ws_bwd = fm.alloc_workspace(s, fm.WS_BACKWARD, dev)
         d_x = torch.empty(s.T, s.d, dtype=s.torch_dtype, device=dev)
@@ -155,8 +157,7 @@ def run_layer(args, cfg, dev, steps, warmup, cpu, restricted):
         d_wg = torch.empty(s.E, s.d, s.f, dtype=torch.float32, device=dev)
         d_wu = torch.empty(s.E, s.d, s.f, dtype=torch.float32, device=dev)
         d_wd = torch.empty(s.E, s.f, s.d, dtype=torch.float32, device=dev)
-    # training keeps the pre-activations A|B [P,2f] of the forward pass for the backward pass
-    act_save = torch.empty(s.P, 2 * s.f, dtype=s.torch_dtype, device=dev) if do_bwd and not args.recompute else None
+    act_save = torch.empty(s.P * 3 * s.f, dtype=s.torch_dtype, device=dev) if keep_act else None
 
     def st_topk():
         fm.fine_topk(s, inp.x, inp.w_router, inp.bias, topk_idx, topk_w, ws_topk)
@@ -409,7 +410,7 @@ def run_layer(args, cfg, dev, steps, warmup, cpu, restricted):
                        " + backward (dgrad, wgrad, gradient of combine weights)" if do_bwd else ""),
                    "flop_per_step": step_flop,
                    "placement": placement_note, "ffn_calls": args.ffn, "launch": "HIP graph replay" if args.graph else "eager", "backward": bool(do_bwd),
-                   "pre_activations": (None if not do_bwd else "recomputed" if args.recompute else "saved by the forward pass")},
+                   "pre_activations": (None if not do_bwd else "recomputed" if args.recompute else "saved by the forward pass, with H")},
         "rank_load": rank_load, "roofline": roofline, "cpu_baseline": cpu_baseline, "detail": detail,
     }
     return line

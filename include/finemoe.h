@@ -52,7 +52,8 @@ enum { FINE_F32 = 0, FINE_BF16 = 1 };
 /* flags (fine_shape.flags).  Other bits are measurement and test switches declared in
  * finemoe_measure.h; they are not part of this contract and are zero in normal use. */
 enum {
-    FINE_FLAG_LOCALITY = 1       /* run the local pass of Algorithm 1 first: a rank keeps its own tokens up to its replica load */
+    FINE_FLAG_LOCALITY = 1,      /* run the local pass of Algorithm 1 first: a rank keeps its own tokens up to its replica load */
+    FINE_FLAG_ACT_SAVE_H = 16    /* act_save holds H behind the pre-activations (fine_grouped_ffn, fine_backward) */
 };
 
 /* which entry point a workspace is for */
@@ -212,6 +213,9 @@ int fine_permute(const fine_shape* shape, const void* x, const int32_t* pair_of_
  *   A = X W_gate[e], B = X W_up[e], H = silu(A) * B (rounded to dtype), Y = H W_down[e].
  *   x_perm [P,d]; w_gate, w_up [E,d,f]; w_down [E,f,d]; y_perm [P,d] out;
  *   act_save NULL or [P,2f] dtype out: columns [0,f) = A, [f,2f) = B (for fine_backward).
+ *        With FINE_FLAG_ACT_SAVE_H the buffer has P*3f elements: [P,2f] as above, followed by
+ *        H [P,f].  H then lives there instead of in `ws` (nothing more is written or read than
+ *        without the flag), and fine_backward called with the same flag takes it from there.
  * Rows of other ranks are left untouched.
  */
 int fine_grouped_ffn(const fine_shape* shape, int32_t rank,
@@ -233,7 +237,11 @@ int fine_combine(const fine_shape* shape, const void* y_perm, const int32_t* row
  * replicas with a data-parallel all-reduce (Section 2.2); on one GPU the replicas share one fp32
  * accumulator per expert, summed in ascending rank order.
  *   d_out [T,d] dtype; x_perm, y_perm [P,d] as produced by the forward entry points;
- *   act_save [P,2f] as written by fine_grouped_ffn, or NULL (then recomputed into ws);
+ *   act_save [P,2f] as written by fine_grouped_ffn, or NULL (then recomputed into ws); with
+ *        FINE_FLAG_ACT_SAVE_H: P*3f elements, [P,2f] followed by H [P,f], as written by
+ *        fine_grouped_ffn under the same flag (the forward pass's H, rounded once from the fp32
+ *        accumulators, is then read for the gradient of W_down instead of an H derived again
+ *        from the rounded A and B: the two differ in the last bit of a bf16 value here and there);
  *   d_x [T,d] dtype out: d_x[t] = sum_k dXp[row_of_pair[t*K+k]];
  *   d_topk_w [T,K] fp32 out: <d_out[t], y_perm[row_of_pair[t*K+k]]> (the router itself is
  *        not differentiated);

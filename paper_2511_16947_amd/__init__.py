@@ -27,6 +27,7 @@ FINE_INFEASIBLE = -4
 FINE_HIP_ERROR = -5
 FINE_F32, FINE_BF16 = 0, 1
 FLAG_LOCALITY = 1
+FLAG_ACT_SAVE_H = 16
 # measurement and test switches (include/finemoe_measure.h; not part of the contract)
 FLAG_SIMPLE_FFN, FLAG_ONLY_GEMM1, FLAG_ONLY_GEMM2 = 2, 4, 8
 FLAG_TILE_SHIFT, FLAG_BWD_STAGE_SHIFT = 8, 12

@@ -105,7 +105,7 @@ __device__ __forceinline__ void bwd_dh_body(const uint16_t* __restrict__ dy, con
             const size_t row = (size_t)te.row0 + m;
             *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + col) = g.da;
             *reinterpret_cast<uint2*>(dact + row * (size_t)(2 * f) + f + col) = g.db;
-            *reinterpret_cast<uint2*>(h + row * (size_t)f + col) = g.hh;
+            if (h != nullptr) *reinterpret_cast<uint2*>(h + row * (size_t)f + col) = g.hh;      // (block-uniform)
         };
         auto acc_val = [&](auto mi, auto t, auto rg, auto q) { return acc[mi.value][t.value][4 * rg.value + q.value]; };
         if constexpr (W8)
@@ -393,6 +393,16 @@ int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d
     auto* tiles = reinterpret_cast<TileEntry*>(ws + L.tiles);
     auto* count = reinterpret_cast<int32_t*>(ws + L.count);
     const uint16_t* act = reinterpret_cast<const uint16_t*>(act_save);
+    // H for the weight gradients of W_down: kept by the forward pass behind the pre-activations, or written by
+    // the GEMM 1 that recomputes them, or else derived from A and B again in the epilogue of the dH kernel
+    const uint16_t* h_in = h;
+    uint16_t* h_out = h;
+    if (act != nullptr && (s.flags & FINE_FLAG_ACT_SAVE_H)) {
+        h_in = act + (size_t)s.T * s.K * 2 * s.f;
+        h_out = nullptr;
+    } else if (act == nullptr) {
+        h_out = nullptr;
+    }
 
     // A call for one rank of several touches only that rank's rows; their intermediate results stay
     // in the workspace, and the call for the last rank gathers d_x from the rows of all ranks.
@@ -415,7 +425,7 @@ int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d
     if (tile == 0) tile = seg_rows >= 384.0 ? 3 : (seg_rows >= 96.0 ? 2 : 1);
 #define FINE_DGRAD(WAM, WAN, WMM, WNN)                                                                        \
     FINE_TRY((run_dgrad<WAM, WAN, WMM, WNN>(s, rank_lo, rank_hi, dy, act, (const uint16_t*)wg, (const uint16_t*)wu, \
-                                            (const uint16_t*)wd, seg_off, dact, h, dxp, tiles, count, L.max_tiles,  \
+                                            (const uint16_t*)wd, seg_off, dact, h_out, dxp, tiles, count, L.max_tiles, \
                                             on(2), on(3), st)))
     if (on(2) || on(3)) {
         if (tile == 3) FINE_DGRAD(2, 4, 4, 2);
@@ -426,9 +436,9 @@ int launch_backward(const fine_shape& s, int rank_lo, int rank_hi, const void* d
     // weight-gradient tiles span the weight matrices, not the segments
     if (on(4)) {
         if (s.d >= 256 && s.f >= 256 && tile != 1)
-            FINE_TRY((run_wgrad<2, 4, 4, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+            FINE_TRY((run_wgrad<2, 4, 4, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h_in, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
         else
-            FINE_TRY((run_wgrad<2, 2, 2, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
+            FINE_TRY((run_wgrad<2, 2, 2, 2>(s, rank_lo, rank_hi, (const uint16_t*)x_perm, dy, dact, h_in, seg_off, d_wg, d_wu, d_wd, accumulate, st)));
     }
     if (on(5) && rank_hi == s.G) FINE_TRY(launch_permute_bwd(s, dxp, row_of_pair, d_x, st));
     return FINE_OK;

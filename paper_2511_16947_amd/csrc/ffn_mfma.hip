@@ -391,7 +391,11 @@ int launch_ffn_mfma(const fine_shape& s, int rank_lo, int rank_hi, const void* x
                     const void* wg, const void* wu, const void* wd, const int32_t* seg_off,
                     void* y_perm, void* act_save, char* ws, hipStream_t st) {
     const FfnWs L = ffn_ws_layout(s);
-    return launch_ffn_parts(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, ws + L.h, y_perm, act_save,
+    // H: in the workspace, or behind the saved pre-activations when the caller keeps it for the backward pass
+    void* h_buf = ws + L.h;
+    if ((s.flags & FINE_FLAG_ACT_SAVE_H) && act_save != nullptr)
+        h_buf = static_cast<char*>(act_save) + (size_t)s.T * s.K * 2 * s.f * elem_size(s.dtype);
+    return launch_ffn_parts(s, rank_lo, rank_hi, x_perm, wg, wu, wd, seg_off, h_buf, y_perm, act_save,
                             reinterpret_cast<TileEntry*>(ws + L.tiles), reinterpret_cast<int32_t*>(ws + L.count),
                             L.max_tiles, reinterpret_cast<float*>(ws + L.sk), !(s.flags & FINE_FLAG_ONLY_GEMM2), !(s.flags & FINE_FLAG_ONLY_GEMM1), st);
 }

@@ -173,6 +173,8 @@ static int ffn_simple_t(const fine_shape& s, int rank_lo, int rank_hi, const voi
     auto* tiles = reinterpret_cast<TileEntry*>(ws + L.tiles);
     auto* count = reinterpret_cast<int32_t*>(ws + L.count);
     T* h = reinterpret_cast<T*>(ws + L.h);
+    if ((s.flags & FINE_FLAG_ACT_SAVE_H) && act_save != nullptr)      // H behind the saved pre-activations
+        h = static_cast<T*>(act_save) + (size_t)s.T * s.K * 2 * s.f;
     FINE_TRY(launch_tile_map(s, seg_off, rank_lo, rank_hi, 64, tiles, count, L.max_tiles, st));
     const int grid = 2048;
     hipLaunchKernelGGL((k_gemm_simple<T, 0>), dim3(grid), dim3(256), 0, st, (const T*)x_perm, s.d, (const T*)wg,

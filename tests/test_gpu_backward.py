@@ -49,14 +49,23 @@ def small_train_cfgs():
 
 @pytest.mark.parametrize("cfg", small_train_cfgs(), ids=lambda c: c.name)
 @pytest.mark.parametrize("tile", [0, 1, 2, 3])
-@pytest.mark.parametrize("saved", [False, True])
+@pytest.mark.parametrize("saved", [False, True, "with_h"])
 def test_backward_elementwise(cfg, tile, saved):
+    """saved: the pre-activations are recomputed by the backward pass (False), kept by the forward pass (True),
+    or kept together with H (FINE_FLAG_ACT_SAVE_H)."""
     print("backward case", cfg.name, "tile", tile, "act_save", saved, flush=True)
     inp = wl.make_inputs(cfg, DEV)
-    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+    with_h = saved == "with_h"
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8) | (fm.FLAG_ACT_SAVE_H if with_h else 0))
     if saved:
-        layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+        layer.act_save = torch.full((cfg.P * (3 if with_h else 2) * cfg.f,), float("nan"), dtype=torch.bfloat16, device=DEV)
     layer.forward()
+    if with_h:
+        # behind the pre-activations lies H = silu(A) * B of every row
+        ab = layer.act_save[:cfg.P * 2 * cfg.f].view(cfg.P, 2 * cfg.f).double()
+        a, b = ab[:, :cfg.f], ab[:, cfg.f:]
+        h = layer.act_save[cfg.P * 2 * cfg.f:].view(cfg.P, cfg.f).double()
+        assert max_rel_err(h.cpu().numpy(), (a / (1.0 + torch.exp(-a)) * b).cpu().numpy()) <= TOL
     bwd = GpuBackward(layer)
     bwd.run()
 
@@ -111,7 +120,7 @@ def test_backward_under_a_restricted_placement(tile):
 
 
 @pytest.mark.parametrize("tile", [0, 3])
-@pytest.mark.parametrize("saved", [False, True])
+@pytest.mark.parametrize("saved", [False, True, "with_h"])
 def test_backward_rank_by_rank(tile, saved):
     """One fine_backward call per rank in ascending order (rank 0 overwriting the weight gradients,
     the others adding to them) against one call for all ranks: d_x and d_topk_w bit-equal, the weight
@@ -121,9 +130,10 @@ def test_backward_rank_by_rank(tile, saved):
                     bias_kind="scaled_z", bias_scale=1.5)
     inp = wl.make_inputs(cfg, DEV)
     place = torch.from_numpy(wl.placement_z2xz4()).to(DEV)
-    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8))
+    with_h = saved == "with_h"
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (tile << 8) | (fm.FLAG_ACT_SAVE_H if with_h else 0))
     if saved:
-        layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+        layer.act_save = torch.empty(cfg.P * (3 if with_h else 2) * cfg.f, dtype=torch.bfloat16, device=DEV)
     layer.forward(place=place)
     whole = GpuBackward(layer)
     whole.run()
@@ -155,8 +165,8 @@ def test_backward_full_size_cfg5():
     cfg = wl.CONFIGS["cfg5_train"]
     print("full-size backward cfg5", flush=True)
     inp = wl.make_inputs(cfg, DEV)
-    layer = GpuLayer(cfg, inp)
-    layer.act_save = torch.empty(cfg.P, 2 * cfg.f, dtype=torch.bfloat16, device=DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | fm.FLAG_ACT_SAVE_H)      # as bench.py runs it: H kept by the forward pass
+    layer.act_save = torch.empty(cfg.P * 3 * cfg.f, dtype=torch.bfloat16, device=DEV)
     layer.forward(per_rank=True)
     bwd = GpuBackward(layer)
     bwd.run()
