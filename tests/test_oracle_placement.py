@@ -47,6 +47,14 @@ def test_mix32_is_a_bijection_that_mixes():
     assert 14 < np.mean(flips) < 18
 
 
+def test_mix32_gives_the_published_values_of_the_murmur3_finaliser():
+    """The 32-bit finaliser of MurmurHash3 (fmix32), which mix32 is stated to be, maps 0 to 0, 1 to 0x514E28B7 and
+    2^32 - 1 to 0x81F16F39 (values quoted wherever the finaliser is tabulated); a wrong shift or multiplier gives others."""
+    assert placement.mix32(0) == 0
+    assert placement.mix32(1) == 0x514E28B7
+    assert placement.mix32(0xFFFFFFFF) == 0x81F16F39
+
+
 def test_rank_keys_differ_between_candidates_experts_and_ranks():
     keys = {placement.rank_key(7, c, e, g) for c in range(8) for e in range(16) for g in range(16)}
     assert len(keys) >= 8 * 16 * 16 - 1          # 2048 draws from 2^32: a collision is a 1 in 2000 event
