@@ -225,23 +225,27 @@ def test_a_small_rest_of_tiles_is_cut_into_few_parts(tile, d, f, T, parts):
         assert torch.equal(layer.y_perm, first)
 
 
-def test_units_of_a_long_launch_are_handed_out_from_queues():
-    """More than two rounds of tiles in both GEMMs of one call (572 column-by-row tiles on 256 blocks,
-    the rest cut along k): from the second round on the blocks take their tiles from the per-XCD
-    queues, whoever is free first.  Every element and every row against the oracle, ragged row
+@pytest.mark.parametrize("d,f,both", [(5632, 2816, True), (1024, 2560, False)])
+def test_units_of_a_long_launch_are_handed_out_from_queues(d, f, both):
+    """More than two rounds of tiles in one launch (26 row tiles: 572 tiles in both GEMMs on 256 blocks with the
+    rest cut along k over the whole grid; or 520 tiles in GEMM 1 with its 16 k-tiles and a rest of 8 tiles cut into
+    two parts each): from the second round on the blocks take their tiles, and the parts of the rest, from the
+    per-XCD queues, whoever is free first.  Every element and every row against the oracle, ragged row
     tiles of several lengths among whole ones, the call for all ranks and the calls rank by rank,
     and bit-stable from run to run (which block computes a tile must not matter)."""
-    cfg = wl.LayerConfig("queues", 2688, 5632, 2816, 8, 2, 2, "bf16", 13, "scaled_z", 1.0)
+    cfg = wl.LayerConfig("queues", 2688, d, f, 8, 2, 2, "bf16", 13, "scaled_z", 1.0)
     inp = wl.make_inputs(cfg, DEV)
     layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (3 << 8))
-    print("queue case", flush=True)
+    print("queue case d", d, "f", f, flush=True)
     layer.y_perm.fill_(float("nan"))
     layer.forward()
     idx = layer.topk_idx.cpu().numpy()
     want = check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G)
     seg = np.diff(want["seg_off"], axis=1)
     row_tiles = int((-(-seg // 256)).sum())
-    assert row_tiles * (cfg.f // 128) > 512 and row_tiles * (cfg.d // 256) > 512      # the case is what it says
+    assert row_tiles * (cfg.f // 128) > 512 and (not both or row_tiles * (cfg.d // 256) > 512)      # the case is what it says
+    if not both:      # few parts: a rest of at most 128 tiles, 16 k-tiles
+        assert cfg.d == 1024 and 0 < row_tiles * (cfg.f // 128) - 512 <= 128
     assert ((seg % 256) != 0).sum() >= 4
     weights_of = weights_of_factory(inp)
     ref_y = moe.grouped_ffn(moe.permute(to64(inp.x), want["pair_of_row"], cfg.K), want["seg_off"], weights_of)
