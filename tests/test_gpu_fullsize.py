@@ -1,7 +1,7 @@
 """Full-size forward parity on the four bf16 workloads, in the launch configuration
-bench.py times (one fine_grouped_ffn call per logical rank): schedules bit-exact on
-the whole routing table, and EVERY element of y_perm and of out against the oracle,
-tensor-wide and row by row."""
+bench.py times (one fine_grouped_ffn call per logical rank) and in one call for all ranks:
+schedules bit-exact on the whole routing table, and EVERY element of y_perm and of out
+against the oracle, tensor-wide and row by row."""
 import numpy as np
 import pytest
 import torch
@@ -78,6 +78,22 @@ def test_full_size_forward(name):
     ref_pair = pair_reference(cfg, inp, idx, want)
     print("  oracle done", flush=True)
     ref_out = check_every_element(cfg, layer, want, ref_pair, w)
+
+    # the same rows in ONE call for all ranks (thousands of tiles of every length in one launch, handed out to the
+    # blocks as they become free): every element again, twice, bit-equal between the two runs
+    layer.y_perm.fill_(float("nan"))
+    layer.out.fill_(float("nan"))
+    layer.ffn(-1)
+    layer.combine()
+    torch.cuda.synchronize()
+    print("  one call for all ranks:", flush=True)
+    check_every_element(cfg, layer, want, ref_pair, w)
+    first = layer.y_perm.clone()
+    layer.y_perm.fill_(float("nan"))
+    layer.ffn(-1)
+    torch.cuda.synchronize()
+    assert torch.equal(layer.y_perm.view(torch.int16), first.view(torch.int16))
+    del first
 
     # the scheduled reference is the dense per-token definition (sampled tokens, hottest expert included)
     rng = np.random.default_rng(123)
