@@ -140,23 +140,58 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
     // gains 30 %, half a round of 64-step GEMM 1 tiles a little); on the 128-row tile, whose
     // workloads stream weights from HBM, the cut only pays for long k ranges (32 steps).
     const int whole_rounds = (total / nblk) * nblk;
-    const bool cut = W8 && (long long)nk * (nblk - (total - whole_rounds)) > (long long)(WM == 4 ? 16 : 32) * nblk;
+    const bool cut_even = W8 && (long long)nk * (nblk - (total - whole_rounds)) > (long long)(WM == 4 ? 16 : 32) * nblk;
     // Below that break-even a small rest would still cost a whole extra round (24 of 280 tiles of 32
     // steps: one more tile time with 232 CUs idle).  Spreading so few steps over the whole grid would
     // leave each tile in ten parts for its last block to add up; instead every rest tile is cut into 2
     // or 4 parts of at least 8 steps, part t + p * rest being k range p of rest tile t ("few parts").
     const int rest_if = total - whole_rounds;
+    // A rest of more than half a round (and GEMMs whose tiles share weight panels: the 256-row tile) is cut in
+    // GROUPS instead: q consecutive rest tiles (same column, adjacent rows) share q + 1 parts of q nk / (q + 1)
+    // steps, q = ceil(rest / (nblk - rest)), so that every tile is made of exactly two parts (one write, one
+    // read, the last one keeps its own), no part touches more than two tiles, and the tiles of a group
+    // walk their weight panel nearly together.  Parts are a little longer than with the even cut over the
+    // whole grid (72 -> 86 of 128 steps for 144 tiles) and some blocks stay idle, but measured on one expert
+    // with n whole row tiles at the training shape's GEMM 2 (8 column tiles, 128 k-steps) the even cut took
+    // 192-241 us for n = 17 ... 22 where its step count says 110-145.
+    int grp = 0;
+    if (W8 && WM == 4 && 2 * rest_if > nblk && rest_if < nblk) {
+        const int q = (rest_if + (nblk - rest_if) - 1) / (nblk - rest_if);
+        if (nk > 16 * (q + 1)) grp = q;      // what a part saves against a whole tile, nk / (q + 1) steps, must pay for a partial tile
+    }
+    const bool cut = cut_even && grp == 0;
     int few = 0;
-    if (W8 && !cut && rest_if > 0)
+    if (W8 && !cut && grp == 0 && rest_if > 0)
         for (int p = 4; p >= 2 && few == 0; p >>= 1)
             if (rest_if * p <= nblk && nk % p == 0 && nk / p >= 8) few = p;
-    const int full = (cut || few) ? whole_rounds : total;
+    const int full = (cut || few || grp) ? whole_rounds : total;
     const int rest = total - full;
     const int per = (rest * nk + nblk - 1) / nblk;
-    const int nparts = cut ? nblk : rest * few;
+    const int n_groups = grp ? (rest + grp - 1) / grp : 0;
+    const int nparts = cut ? nblk : grp ? rest + n_groups : rest * few;
     int32_t* counters = count + kSkCounterOffset;      // arrivals per rest tile
     int32_t* ready = count + kSkReadyOffset;           // parts written per rest tile
-    auto slot_of = [&](int part, int t) { return few ? part * 2 : part * 2 + (((part * per) / nk) == t ? 0 : 1); };
+    // steps [u0, u1) of the sequence of rest tiles (tile t = steps [t nk, (t + 1) nk)) that part `part` computes
+    auto part_range = [&](int part, int& u0, int& u1) {
+        if (grp) {
+            const int g = part / (grp + 1), i = part - g * (grp + 1);
+            const int tiles_g = min(grp, rest - g * grp);      // the last group may be shorter
+            const int steps_g = tiles_g * nk;
+            u0 = g * grp * nk + (int)((long long)i * steps_g / (tiles_g + 1));
+            u1 = g * grp * nk + (int)((long long)(i + 1) * steps_g / (tiles_g + 1));
+            if (i > tiles_g) u0 = u1 = 0;                      // (no such part: a shorter last group has fewer)
+        } else {
+            u0 = min(rest * nk, part * per);
+            u1 = min(rest * nk, u0 + per);
+        }
+    };
+    // a part's slot for its piece of tile t: 0 if the part begins in t, else 1 (few parts: one piece per part)
+    auto slot_of = [&](int part, int t) {
+        if (few) return part * 2;
+        int u0, u1;
+        part_range(part, u0, u1);
+        return part * 2 + (u0 / nk == t ? 0 : 1);
+    };
     // Partial sums travel as 16-byte buffer stores and loads with the sc0 sc1 cache policy: they
     // are written through and read past the per-XCD L2 one by one, so no cache-wide write-back or
     // invalidate (a fence) is needed, which would cost every block on the XCD its cached operand
@@ -186,9 +221,9 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
             if (kn != nk) {
                 const int t = work - full;
                 // the parts that hold pieces of tile t: first, first + step, ... (n_parts of them)
-                const int first = few ? t : (t * nk) / per;
+                const int first = few ? t : grp ? (t / grp) * (grp + 1) + t % grp : (t * nk) / per;
                 const int step = few ? rest : 1;
-                const int n_parts = few ? few : (t * nk + nk - 1) / per - first + 1;
+                const int n_parts = few ? few : grp ? 2 : (t * nk + nk - 1) / per - first + 1;
                 // Whoever arrives last (everybody else has left its k-loop by then) adds the parts up; the
                 // others write theirs to their slots and then count themselves ready.  The tile is
                 // part 0 + part 1 + part 2 + ... in that order whoever adds: if the last one holds part 0 or
@@ -273,8 +308,8 @@ __device__ __forceinline__ void ffn_gemm_body(const uint16_t* __restrict__ A, in
                 piece(full + part % rest, (part / rest) * kn, kn, part, true);
             } else {
                 const int part = v - full;
-                int u = part * per;
-                const int u1 = min(rest * nk, u + per);
+                int u, u1;
+                part_range(part, u, u1);
                 if (u >= u1) request();      // (an empty part at the end of the sequence)
                 while (u < u1) {
                     const int t = u / nk, kb = u - t * nk, kn = min(nk - kb, u1 - u);

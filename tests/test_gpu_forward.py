@@ -225,6 +225,36 @@ def test_a_small_rest_of_tiles_is_cut_into_few_parts(tile, d, f, T, parts):
         assert torch.equal(layer.y_perm, first)
 
 
+@pytest.mark.parametrize("T", [1280, 1200])
+def test_a_rest_above_half_a_round_is_cut_in_groups(T):
+    """160 tiles of 50 k-tiles on 256 blocks in GEMM 1 (five row tiles, the last one whole or ragged, 32 column
+    tiles): groups of two tiles share three parts, every tile is the sum of two parts.  GEMM 2 (65 tiles of 64
+    k-tiles) takes the even cut over the whole grid.  Every element and every row against the oracle, and
+    bit-stable from run to run."""
+    cfg = wl.LayerConfig("groups", T, 3200, 4096, 1, 1, 1, "bf16", 17, "scaled_z", 0.5)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (3 << 8))
+    print("grouped-cut case T", T, flush=True)
+    layer.y_perm.fill_(float("nan"))
+    layer.forward()
+    idx = layer.topk_idx.cpu().numpy()
+    want = check_schedule_against_oracle(layer.sb, idx, cfg.E, cfg.G)
+    rest, nk = -(-T // 256) * (cfg.f // 128), cfg.d // 64
+    q = -(-rest // (256 - rest))
+    assert 128 < rest < 256 and nk > 16 * (q + 1)      # the case is what it says
+    weights_of = weights_of_factory(inp)
+    ref_y = moe.grouped_ffn(moe.permute(to64(inp.x), want["pair_of_row"], cfg.K), want["seg_off"], weights_of)
+    got = to64(layer.y_perm)
+    assert max_rel_err(got, ref_y) <= tol_for(cfg)
+    assert max_rel_err_rows(got, ref_y) <= tol_for(cfg)
+    first = layer.y_perm.clone()
+    for _ in range(3):
+        layer.y_perm.zero_()
+        layer.ffn(-1)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.y_perm, first)
+
+
 @pytest.mark.parametrize("d,f,both", [(5632, 2816, True), (1024, 2560, False)])
 def test_units_of_a_long_launch_are_handed_out_from_queues(d, f, both):
     """More than two rounds of tiles in one launch (26 row tiles: 572 tiles in both GEMMs on 256 blocks with the
