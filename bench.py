@@ -32,10 +32,10 @@ HBM_PEAK_GBS = 8000.0
 # Counter readings (mean KiB per launch under rocprofv3 --pmc; the summaries under profiles/ give the
 # commands), scaled by what the same counters read for --copy-calibration: FETCH_SIZE 0.5 per byte read,
 # WRITE_SIZE 1.0 per byte written.  GEMM 1 of a rank on cfg2_mixtral; the weight-gradient kernel of cfg5_train.
-GEMM1_TRAFFIC_BYTES = {"cfg2_mixtral": int(751482.5 * 1024 * 2.0 + 80773.3 * 1024 * 1.0),      # profiles/ffn_gemm1_w8_cfg2_mixtral_trace_and_counters.md
-                       "cfg4_dsv3": int(0.759e9),                                            # profiles/ffn_per_rank_cfg4_dsv3_trace_and_counters.md
-                       "cfg5_train": int(419380.4 * 1024 * 2.0 + 210360.1 * 1024 * 1.0)}     # profiles/train_step_cfg5_train_hbm_counters.md
-WGRAD_TRAFFIC_BYTES = {"cfg5_train": int(5146359.4 * 1024 * 2.0 + 12582912.6 * 1024 * 1.0)}  # profiles/train_step_cfg5_train_hbm_counters.md
+GEMM1_TRAFFIC_BYTES = {"cfg2_mixtral": int(743163.3 * 1024 * 2.0 + 80744.1 * 1024 * 1.0),      # profiles/ffn_gemm1_w8_cfg2_mixtral_trace_and_counters.md
+                       "cfg4_dsv3": int(0.755e9),                                            # profiles/ffn_per_rank_cfg4_dsv3_trace_and_counters.md
+                       "cfg5_train": int(424611.9 * 1024 * 2.0 + 210386.8 * 1024 * 1.0)}     # profiles/train_step_cfg5_train_hbm_counters.md
+WGRAD_TRAFFIC_BYTES = {"cfg5_train": int(5188948.7 * 1024 * 2.0 + 12582913.1 * 1024 * 1.0)}  # profiles/train_step_cfg5_train_hbm_counters.md
 BASELINE_METRIC = "MoE layer TFLOP/s per GPU (sched+permute+grouped GEMM+combine); max/mean rank load"
 
 
