@@ -193,3 +193,48 @@ def test_backward_full_size_cfg5():
             e_all, e_row = max_rel_err(ge, ref), max_rel_err_rows(ge, ref)
             print("  expert %d (%d rows) %s: max-rel-err %.3e, worst row %.3e" % (e, load[e], key, e_all, e_row), flush=True)
             assert e_all <= TOL and e_row <= TOL, (key, e)
+
+
+def test_a_training_step_can_be_captured_in_a_graph():
+    """Forward pass (keeping the pre-activations and H) and backward pass of a small layer whose GEMMs cut tiles along
+    k, captured in one HIP graph: every replay, with eager work and synchronisations in between, gives the bits of
+    the eager run (the partial-sum counters and work queues are cleared and waited for inside the kernels)."""
+    cfg = wl.scaled(wl.CONFIGS["cfg5_train"], name="graph_train", T=512, d=256, f=2560, E=4, K=2, G=2,
+                    bias_kind="scaled_z", bias_scale=1.0)
+    inp = wl.make_inputs(cfg, DEV)
+    layer = GpuLayer(cfg, inp, fm.FLAG_LOCALITY | (3 << 8) | fm.FLAG_ACT_SAVE_H)
+    layer.act_save = torch.empty(cfg.P * 3 * cfg.f, dtype=torch.bfloat16, device=DEV)
+    layer.forward(per_rank=True)                           # eager; also sets every kernel attribute before the capture
+    bwd = GpuBackward(layer)
+    bwd.run()
+    want = [t.clone() for t in (layer.out, bwd.d_x, bwd.d_topk_w, bwd.d_wg, bwd.d_wu, bwd.d_wd)]
+    g = moe.backward_dense(to64(inp.x), layer.topk_idx.cpu().numpy(), to64(layer.topk_w), weights_of_factory(inp),
+                           to64(inp.d_out))
+    assert max_rel_err(to64(bwd.d_x), g["d_x"]) <= TOL
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    L, i = layer, inp
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            layer.topk()
+            layer.sched(None)
+            layer.permute()
+            for r in range(cfg.G):
+                layer.ffn(r)
+            layer.combine()
+            fm.fine_backward(L.shape, -1, i.d_out, L.x_perm, L.y_perm, L.act_save, i.w_gate, i.w_up, i.w_down,
+                             L.sb.row_of_pair, L.sb.pair_of_row, L.sb.seg_off, L.topk_w, bwd.d_x, bwd.d_topk_w,
+                             bwd.d_wg, bwd.d_wu, bwd.d_wd, False, bwd.ws)
+    torch.cuda.current_stream().wait_stream(side)
+    for n in range(3):
+        for t in (layer.out, bwd.d_x, bwd.d_topk_w, bwd.d_wg, bwd.d_wu, bwd.d_wd, layer.act_save):
+            t.fill_(float("nan"))
+        layer.topk()                                       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((layer.out, bwd.d_x, bwd.d_topk_w, bwd.d_wg, bwd.d_wu, bwd.d_wd), want):
+            assert torch.equal(got.view(torch.int32 if got.dtype == torch.float32 else torch.int16),
+                               ref.view(torch.int32 if ref.dtype == torch.float32 else torch.int16)), n
